@@ -1,0 +1,180 @@
+/*
+ * tdp.h - C ABI of the MI355X pipeline-stage library.
+ *
+ * One "stage" is a contiguous slice of a Llama-style model's decoder layers held by one GPU
+ * (paper Sec. 2.2.3: pipeline parallelism splits the model layer-wise, each device owning a
+ * subset of layers).  A stage is told which batch to run and in which phase (Sec. 3.2: the
+ * engine packs prompts for the prefill phase and decode steps for the decode phase; a worker
+ * only knows what to compute); batches are never mixed (separate batching, Sec. 2.3, Sec. 3.1).
+ * Hidden states come in from the previous stage and go out to the next: no embedding, no final
+ * norm, no LM head.
+ *
+ * Conventions
+ *  - All functions return TDP_OK (0) or a negative error code; tdp_last_error() gives a
+ *    thread-local message for the most recent failure.
+ *  - Argument checks run on the host before any GPU work, so a bad argument never launches.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host addresses.
+ *  - bf16 is the raw 16-bit brain-float encoding; matrices are row-major.
+ *  - Calls that take a `stream` (a hipStream_t passed as void*, NULL = the default stream) only
+ *    enqueue work and return; nothing synchronises with the host.  One stage must not be driven
+ *    from two streams at once: its scratch buffers are shared.
+ *  - The caller owns page allocation: which physical page belongs to which request is the
+ *    engine's business (Sec. 3.2.1).  The stage only writes the slot the tables name.
+ *    Contents of device-side tables are trusted: a page id outside [0, num_pages) or a
+ *    position beyond 16 * max_pages_per_seq is undefined behaviour.
+ */
+#ifndef TDP_H_
+#define TDP_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TDP_API __attribute__((visibility("default")))
+
+#define TDP_OK       0
+#define TDP_EINVAL  (-1)   /* null pointer, bad shape, size beyond the configured maximum */
+#define TDP_ENOMEM  (-2)   /* device or host allocation failed */
+#define TDP_EHIP    (-3)   /* a HIP runtime call failed (message holds the HIP error string) */
+
+/* weight identifiers for tdp_stage_set_weight */
+#define TDP_WQ      0      /* [d_model, n_q_heads*head_dim]  */
+#define TDP_WK      1      /* [d_model, n_kv_heads*head_dim] */
+#define TDP_WV      2      /* [d_model, n_kv_heads*head_dim] */
+#define TDP_WO      3      /* [n_q_heads*head_dim, d_model]  */
+#define TDP_WG      4      /* [d_model, d_ff]   gate         */
+#define TDP_WU      5      /* [d_model, d_ff]   up           */
+#define TDP_WD      6      /* [d_ff, d_model]   down         */
+#define TDP_G_ATTN  7      /* [d_model] RMSNorm gain before attention */
+#define TDP_G_MLP   8      /* [d_model] RMSNorm gain before the MLP   */
+
+#define TDP_F32     0
+#define TDP_BF16    1
+
+#define TDP_HOST    0
+#define TDP_DEVICE  1
+
+typedef struct tdp_stage tdp_stage;   /* opaque: owns weights, KV pools and scratch (all in HBM) */
+
+typedef struct tdp_stage_config {
+  int32_t n_layers;            /* decoder layers in this stage (>= 1) */
+  int32_t d_model;             /* multiple of 64 */
+  int32_t n_q_heads;           /* multiple of n_kv_heads; group size n_q_heads/n_kv_heads <= 16 */
+  int32_t n_kv_heads;
+  int32_t head_dim;            /* 64 or 128 */
+  int32_t d_ff;                /* SwiGLU width, multiple of 4 */
+  float   rms_eps;
+  float   rope_base;
+  int32_t page_size;           /* tokens per KV page; must be 16 */
+  int32_t num_pages;           /* physical pages per layer in the KV pool */
+  int32_t max_batch;           /* largest decode batch */
+  int32_t max_tokens;          /* largest packed prefill token count */
+  int32_t max_seqs;            /* largest number of prompts in one prefill */
+  int32_t max_pages_per_seq;   /* width of a block-table row */
+} tdp_stage_config;
+
+/* Version of this ABI (bumped on incompatible change). */
+TDP_API int tdp_abi_version(void);
+
+/* Message for the calling thread's most recent error ("" if none).  Never NULL. */
+TDP_API const char* tdp_last_error(void);
+
+/*
+ * Create a stage: allocates weights (zeroed), per-layer K and V pools and scratch on the current
+ * HIP device.  `*out` is set only on success.  Errors: TDP_EINVAL (bad config), TDP_ENOMEM,
+ * TDP_EHIP.  The config is checked before any HIP call.
+ */
+TDP_API int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out);
+
+/* Free everything the stage owns.  NULL is allowed.  Synchronises the device first. */
+TDP_API void tdp_stage_destroy(tdp_stage* st);
+
+/*
+ * Load one weight.  `src` is a row-major [rows, cols] = [in, out] matrix (y = x W) or a vector
+ * [rows] with cols = 1, of type `dtype` (TDP_F32 or TDP_BF16; fp32 is rounded to bf16 with
+ * round-to-nearest-even, gains are kept in fp32), living where `mem` says (TDP_HOST or
+ * TDP_DEVICE).  The library repacks it once into its own MFMA-friendly layout; `src` is not
+ * referenced after the call returns (the call synchronises).  Shapes must match the config.
+ */
+TDP_API int tdp_stage_set_weight(tdp_stage* st, int32_t layer, int32_t which, const void* src,
+                         int32_t dtype, int32_t mem, int64_t rows, int64_t cols);
+
+/*
+ * Raw access to one layer's KV pools, for tests that poison, inject or dump them.
+ * Layout (bf16):  K pool [num_pages][n_kv_heads][16][head_dim]
+ *                 V pool [num_pages][n_kv_heads][head_dim][16]   (token slot fastest)
+ * Keys are stored after the rotary embedding.  `*bytes` = size of EACH pool.
+ */
+TDP_API int tdp_stage_kv_pool(tdp_stage* st, int32_t layer, void** k_dev, void** v_dev, int64_t* bytes);
+
+/*
+ * Copy K/V between packed logical order and the pages (the path a recompute-free migration or a
+ * test would use).  k_packed / v_packed: dev bf16 [total_tokens][n_kv_heads][head_dim], the
+ * sequences' tokens concatenated; token t of sequence s (cu_seqlens[s] <= t < cu_seqlens[s+1])
+ * lives at position t - cu_seqlens[s], i.e. page block_tables[s][pos/16], slot pos%16.
+ * cu_seqlens: dev int32 [n_seqs+1]; block_tables: dev int32 [n_seqs][max_pages_per_seq].
+ * import writes pages from the packed arrays, export reads pages into them.
+ */
+TDP_API int tdp_stage_kv_import(tdp_stage* st, int32_t layer, const void* k_packed, const void* v_packed,
+                        const int32_t* cu_seqlens, const int32_t* block_tables, int32_t n_seqs,
+                        int32_t total_tokens, void* stream);
+TDP_API int tdp_stage_kv_export(tdp_stage* st, int32_t layer, void* k_packed, void* v_packed,
+                        const int32_t* cu_seqlens, const int32_t* block_tables, int32_t n_seqs,
+                        int32_t total_tokens, void* stream);
+
+/*
+ * Prefill phase (Sec. 2.1: all prompt tokens are processed concurrently and the KV cache is
+ * initialised).  Runs every layer of the stage over `total_tokens` packed prompt tokens.
+ *   hidden_in    dev bf16 [total_tokens][d_model]   packed var-length prompts
+ *   cu_seqlens   dev int32 [n_seqs+1]               prefix sums of prompt lengths, [0] = 0
+ *   block_tables dev int32 [n_seqs][max_pages_per_seq]; row s needs ceil(len_s/16) valid entries
+ *   hidden_out   dev bf16 [total_tokens][d_model]   (may alias hidden_in)
+ * Every prompt starts at position 0 on an empty cache (no chunked prefill, Sec. 2.3); attention
+ * is causal within a prompt; K (rotated) and V of every token and layer are written to the
+ * pages.  n_seqs <= max_seqs, total_tokens <= max_tokens, each prompt <= 16*max_pages_per_seq.
+ * n_seqs = 0 or total_tokens = 0 is a successful no-op.
+ */
+TDP_API int tdp_stage_prefill(tdp_stage* st, const void* hidden_in, const int32_t* cu_seqlens,
+                      const int32_t* block_tables, int32_t n_seqs, int32_t total_tokens,
+                      void* hidden_out, void* stream);
+
+/*
+ * Decode phase (Sec. 2.1: each step processes one new token per request using the KV cache).
+ *   hidden_in    dev bf16 [batch][d_model]          one token per request
+ *   ctx_lens     dev int32 [batch]                  tokens ALREADY cached for request b; the new
+ *                                                   token takes position ctx_lens[b]
+ *   block_tables dev int32 [batch][max_pages_per_seq]; row b needs ceil((ctx_lens[b]+1)/16) entries
+ *   hidden_out   dev bf16 [batch][d_model]          (may alias hidden_in)
+ * For every layer the new token's K (rotated) and V are appended at page
+ * block_tables[b][ctx/16], slot ctx%16 BEFORE attention, which then spans ctx+1 tokens.
+ * ctx_lens[b] = 0 is legal.  batch <= max_batch; batch = 0 is a successful no-op.  Re-running a
+ * step with the same inputs rewrites the same slots with the same values.
+ */
+TDP_API int tdp_stage_decode(tdp_stage* st, const void* hidden_in, const int32_t* ctx_lens,
+                     const int32_t* block_tables, int32_t batch, void* hidden_out, void* stream);
+
+/*
+ * Diagnostic: one projection GEMM through the library's kernels, out = A * W with W given as
+ * a row-major [K, N] bf16 device matrix (repacked internally on every call: not a fast path).
+ * A dev bf16 [M][K]; out dev bf16 [M][N].  K multiple of 64, N multiple of 4.
+ * tile: 0 = automatic, 1..4 force a tile shape; splits: 0 = automatic, else force the split-K
+ * factor.  epilogue: 0 = plain store, 1 = out = residual + A*W (residual dev bf16 [M][N]).
+ */
+TDP_API int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out, int32_t M, int32_t N,
+                  int32_t K, int32_t epilogue, int32_t tile, int32_t splits, void* stream);
+
+/*
+ * Timing hooks: when enabled, prefill/decode record HIP events around each kernel class on the
+ * call's stream; tdp_stage_timing_read synchronises and returns the summed milliseconds of the
+ * most recent call per class (order: rmsnorm, gemm_qkv, rope_kv, attention, gemm_o, gemm_gate_up,
+ * gemm_down) into ms[7].
+ */
+TDP_API int tdp_stage_timing_enable(tdp_stage* st, int32_t on);
+TDP_API int tdp_stage_timing_read(tdp_stage* st, float* ms /* host [7] */);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TDP_H_ */

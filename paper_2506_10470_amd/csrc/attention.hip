@@ -1,0 +1,324 @@
+// Attention kernels of the stage: paged GQA decode attention (split over the KV range, then
+// merged) and var-len causal prefill attention.  Both read K and V through the block tables.
+//
+// Decode (paper Sec. 2.1): each request contributes one query token that attends to its whole
+// cache, so the kernel streams K/V once from HBM and is bandwidth bound.  The query heads that
+// share a K/V head (GQA, Sec. 4.1) form the 16-wide "N" side of a 16x16x32 MFMA, so every K/V
+// byte is loaded once per group and goes from global memory straight into MFMA operand
+// registers: no LDS and no cross-lane transposes.
+//
+// The trick that avoids transposing the probabilities: scores are formed transposed,
+// S^T[token][q] = K[token][:] . Q[q][:], and the rows of each MFMA tile are assigned to tokens in
+// the order that makes a lane's accumulator elements the 8 consecutive tokens it must supply as
+// the "B" operand of O^T[channel][q] += V^T[channel][token] P^T[token][q].
+#include "tdp_device.h"
+#include "tdp_kernels.h"
+
+namespace tdp {
+
+constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf: exp2 gives exactly 0, no inf-inf
+
+// =====================================================================================
+// Decode: one wave per (chunk of the KV range, kv head, request).
+// =====================================================================================
+template <int DH>
+__global__ __launch_bounds__(64) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
+                                                         int n_q_heads, KvLayout kv,
+                                                         const int32_t* __restrict__ ctx_lens,
+                                                         const int32_t* __restrict__ block_tables,
+                                                         int max_pages_per_seq, float* __restrict__ part_o,
+                                                         float* __restrict__ part_ml, int max_chunks,
+                                                         float scale_log2) {
+  constexpr int KS = DH / 32;   // k-steps of the score MFMA
+  constexpr int DT = DH / 16;   // 16-channel tiles of the output
+  const int chunk = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int n_total = ctx_lens[b] + 1;  // the new token's K/V were appended before this kernel
+  const int t_begin = chunk * kDecodeChunk;
+  if (t_begin >= n_total) return;
+  const int t_end = min(t_begin + kDecodeChunk, n_total);
+  const int Hkv = kv.n_kv_heads;
+  const int G = n_q_heads / Hkv;
+  const int lane = threadIdx.x;
+  const int r16 = lane & 15, kg = lane >> 4;
+  const bf16* kpool = (const bf16*)kv.k_pool;
+  const bf16* vpool = (const bf16*)kv.v_pool;
+
+  bf16x8 qf[KS];
+  {
+    const bf16* qp = qkv + (int64_t)b * ld + (int64_t)(kvh * G + (r16 < G ? r16 : 0)) * DH + kg * 8;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = r16 < G ? ld_bf16x8(qp + kk * 32) : zero_bf16x8();
+  }
+  f32x4 o[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d) o[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = kNegBig, lsum = 0.f;
+
+  const int32_t* bt = block_tables + (int64_t)b * max_pages_per_seq;
+  const int last_page = (n_total - 1) / 16;
+  // token of this lane's row in score tile t: (r16/4)*8 + t*4 + r16%4
+  const int krow0 = (r16 >> 2) * 8 + (r16 & 3);
+
+  for (int tb = t_begin; tb < t_end; tb += 32) {
+    const int p0 = tb >> 4;
+    const int p1 = min(p0 + 1, last_page);  // never dereference a table entry past the last page
+    const int64_t page0 = bt[p0], page1 = bt[p1];
+
+    bf16x8 kf[2][KS];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int tok = krow0 + t * 4;
+      const int64_t page = tok < 16 ? page0 : page1;
+      const bf16* kp = kpool + ((page * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) kf[t][kk] = ld_bf16x8(kp + kk * 32);
+    }
+    bf16x8 vf[DT];
+    {
+      const int64_t page = kg < 2 ? page0 : page1;
+      const bf16* vp = vpool + ((page * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) vf[d] = ld_bf16x8(vp + d * 16 * 16);
+    }
+
+    f32x4 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) s[t] = mfma16(kf[t][kk], qf[kk], s[t]);
+    }
+    // lane holds tokens tb + kg*8 + t*4 + i of column q = r16
+    const int tok_base = tb + kg * 8;
+    float mx = kNegBig;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float v = (tok_base + t * 4 + i < n_total) ? s[t][i] * scale_log2 : kNegBig;
+        s[t][i] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = exp2f(m - m_new);
+    bf16x8 pb;
+    float psum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float pv = exp2f(s[t][i] - m_new);
+        psum += pv;
+        pb[t * 4 + i] = (bf16)pv;
+      }
+    lsum = lsum * alpha + psum;
+    m = m_new;
+    if (tb + 32 > n_total) {  // tail: slots past the context may hold anything, even NaN
+#pragma unroll
+      for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (tok_base + j >= n_total) vf[d][j] = (bf16)0.0f;
+    }
+#pragma unroll
+    for (int d = 0; d < DT; ++d) {
+      o[d] *= alpha;
+      o[d] = mfma16(vf[d], pb, o[d]);
+    }
+  }
+  lsum += __shfl_xor(lsum, 16, 64);
+  lsum += __shfl_xor(lsum, 32, 64);
+
+  if (r16 < G) {
+    const int h = kvh * G + r16;
+    const int64_t slot = ((int64_t)b * n_q_heads + h) * max_chunks + chunk;
+    float* po = part_o + slot * DH + kg * 4;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(po + d * 16) = o[d];
+    if (kg == 0) {
+      part_ml[slot * 2 + 0] = m;
+      part_ml[slot * 2 + 1] = lsum;
+    }
+  }
+}
+
+// Merge the per-chunk partials: out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
+template <int DH>
+__global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __restrict__ part_o,
+                                                               const float* __restrict__ part_ml,
+                                                               const int32_t* __restrict__ ctx_lens,
+                                                               int n_q_heads, int max_chunks,
+                                                               bf16* __restrict__ out, int64_t ldo) {
+  const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
+  const int n_chunks = min((ctx_lens[b] + 1 + kDecodeChunk - 1) / kDecodeChunk, max_chunks);
+  const int64_t base = ((int64_t)b * n_q_heads + h) * max_chunks;
+  float m = kNegBig;
+  for (int k = 0; k < n_chunks; ++k) m = fmaxf(m, part_ml[(base + k) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int k = 0; k < n_chunks; ++k) {
+    const float w = exp2f(part_ml[(base + k) * 2] - m);
+    den += w * part_ml[(base + k) * 2 + 1];
+    num += w * part_o[(base + k) * DH + c];
+  }
+  out[(int64_t)b * ldo + (int64_t)h * DH + c] = (bf16)(num / den);
+}
+
+hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
+                              const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq,
+                              float* part_o, float* part_ml, int max_chunks, void* out, int64_t ldo,
+                              hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
+  dim3 grid(max_chunks, kv.n_kv_heads, batch), mgrid(n_q_heads, batch);
+  if (kv.head_dim == 128) {
+    attn_decode_kernel<128><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
+                                                max_pages_per_seq, part_o, part_ml, max_chunks, scale_log2);
+    attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_chunks,
+                                                        (bf16*)out, ldo);
+  } else {
+    attn_decode_kernel<64><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
+                                               max_pages_per_seq, part_o, part_ml, max_chunks, scale_log2);
+    attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_chunks,
+                                                      (bf16*)out, ldo);
+  }
+  return hipGetLastError();
+}
+
+// =====================================================================================
+// Prefill: one wave per (block of 32 query rows, query head); var-len packed, causal.
+// =====================================================================================
+template <int DH>
+__global__ __launch_bounds__(64) void attn_prefill_kernel(const bf16* __restrict__ qkv, int64_t ld,
+                                                          int n_q_heads, KvLayout kv,
+                                                          const int32_t* __restrict__ cu_seqlens, int n_seqs,
+                                                          const int32_t* __restrict__ block_tables,
+                                                          int max_pages_per_seq, bf16* __restrict__ out,
+                                                          int64_t ldo, float scale_log2) {
+  constexpr int KS = DH / 16;  // k-steps of the score MFMA
+  constexpr int DT = DH / 32;  // 32-channel tiles of the output
+  const int h = blockIdx.y;
+  // locate the sequence that owns query block blockIdx.x
+  int qb = blockIdx.x, s = 0, L = 0;
+  for (; s < n_seqs; ++s) {
+    L = cu_seqlens[s + 1] - cu_seqlens[s];
+    const int nb = (L + 31) >> 5;
+    if (qb < nb) break;
+    qb -= nb;
+  }
+  if (s == n_seqs) return;
+  const int tok0 = cu_seqlens[s];
+  const int q0 = qb * 32;
+  const int Hkv = kv.n_kv_heads;
+  const int kvh = h / (n_q_heads / Hkv);
+  const int lane = threadIdx.x;
+  const int l32 = lane & 31, kg = lane >> 5;
+  const bf16* kpool = (const bf16*)kv.k_pool;
+  const bf16* vpool = (const bf16*)kv.v_pool;
+  const int qpos = q0 + l32;  // this lane's query column (may lie past the end of the prompt)
+
+  bf16x8 qf[KS];
+  {
+    const bf16* qp = qkv + (int64_t)(tok0 + min(qpos, L - 1)) * ld + (int64_t)h * DH + kg * 8;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qf[kk] = ld_bf16x8(qp + kk * 16);
+  }
+  f32x16 o[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o[d][i] = 0.f;
+  float m = kNegBig, lsum = 0.f;
+
+  const int32_t* bt = block_tables + (int64_t)s * max_pages_per_seq;
+  const int last_page = (L - 1) / 16;
+  const int kv_end = min(q0 + 32, L);
+  // token of this lane's row r = l32 in the score tile: (r/16)*16 + ((r%8)/4)*8 + ((r/8)%2)*4 + r%4
+  const int krow = (l32 >> 4) * 16 + ((l32 >> 2) & 1) * 8 + ((l32 >> 3) & 1) * 4 + (l32 & 3);
+
+  for (int kb = 0; kb < kv_end; kb += 32) {
+    const int p0 = kb >> 4;
+    const int p1 = min(p0 + 1, last_page);
+    const int64_t page0 = bt[p0], page1 = bt[p1];
+    f32x16 sc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+    {
+      const int64_t page = krow < 16 ? page0 : page1;
+      const bf16* kp = kpool + ((page * Hkv + kvh) * 16 + (krow & 15)) * DH + kg * 8;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) sc = mfma32(ld_bf16x8(kp + kk * 16), qf[kk], sc);
+    }
+    // element i of this lane is token kb + (i/8)*16 + kg*8 + i%8 of query column qpos
+    float mx = kNegBig;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int tok = kb + (i >> 3) * 16 + kg * 8 + (i & 7);
+      const float v = (tok <= qpos && tok < L) ? sc[i] * scale_log2 : kNegBig;
+      sc[i] = v;
+      mx = fmaxf(mx, v);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = exp2f(m - m_new);
+    bf16x8 pb[2];
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pv = exp2f(sc[i] - m_new);
+      psum += pv;
+      pb[i >> 3][i & 7] = (bf16)pv;
+    }
+    lsum = lsum * alpha + psum;
+    m = m_new;
+    const bool tail = kb + 32 > L;
+#pragma unroll
+    for (int d = 0; d < DT; ++d) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        const int64_t page = st == 0 ? page0 : page1;
+        bf16x8 vf = ld_bf16x8(vpool + ((page * Hkv + kvh) * DH + d * 32 + l32) * 16 + kg * 8);
+        if (tail) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (kb + st * 16 + kg * 8 + j >= L) vf[j] = (bf16)0.0f;
+        }
+        o[d] = mfma32(vf, pb[st], o[d]);
+      }
+    }
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (qpos < L) {
+    const float inv = 1.0f / lsum;
+    bf16* op = out + (int64_t)(tok0 + qpos) * ldo + (int64_t)h * DH + kg * 4;
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[d][g * 4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + d * 32 + g * 8) = v;
+      }
+  }
+}
+
+hipError_t launch_attn_prefill(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
+                               const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
+                               int max_pages_per_seq, void* out, int64_t ldo, hipStream_t s) {
+  if (total_tokens <= 0 || n_seqs <= 0) return hipSuccess;
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
+  dim3 grid((total_tokens + 31) / 32 + n_seqs, n_q_heads);
+  if (kv.head_dim == 128)
+    attn_prefill_kernel<128><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
+                                                 block_tables, max_pages_per_seq, (bf16*)out, ldo, scale_log2);
+  else
+    attn_prefill_kernel<64><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
+                                                block_tables, max_pages_per_seq, (bf16*)out, ldo, scale_log2);
+  return hipGetLastError();
+}
+
+}  // namespace tdp

@@ -1,0 +1,226 @@
+// Bandwidth-trivial kernels of the stage: RMSNorm, rotary embedding fused with the KV-cache
+// append, KV import/export, and the one-time weight repack.
+//
+// The KV cache (paper Sec. 2.1: per-token keys and values kept so that a decode step only
+// processes the new token) is paged in fixed-size pages addressed through per-request block
+// tables.  Physical layout per layer:
+//   K pool  [num_pages][n_kv_heads][page_size][head_dim]   (one token's key contiguous)
+//   V pool  [num_pages][n_kv_heads][head_dim][page_size]   (token index fastest)
+// Keys are stored after rotation.  The V layout puts 8 consecutive tokens of one channel in
+// 16 bytes, which is exactly the MFMA operand of the P*V product in both attention kernels.
+#include "tdp_device.h"
+#include "tdp_kernels.h"
+
+namespace tdp {
+
+// ------------------------------------------------------------------ RMSNorm
+// y = x * g / sqrt(mean(x^2) + eps); one workgroup per row, fp32 statistics.
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16* __restrict__ x, int64_t ldx,
+                                                      const float* __restrict__ gain, float eps, int d,
+                                                      bf16* __restrict__ y, int64_t ldy) {
+  const int row = blockIdx.x;
+  const bf16* xr = x + (int64_t)row * ldx;
+  bf16* yr = y + (int64_t)row * ldy;
+  const int chunks = d / 8;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < chunks; c += 256) {
+    bf16x8 v = ld_bf16x8(xr + c * 8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float f = (float)v[i];
+      ss += f * f;
+    }
+  }
+  __shared__ float red[4];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = red[0] + red[1] + red[2] + red[3];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int c = threadIdx.x; c < chunks; c += 256) {
+    bf16x8 v = ld_bf16x8(xr + c * 8);
+    const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c * 8);
+    const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + c * 8 + 4);
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[i] = (bf16)((float)v[i] * inv * g0[i]);
+      o[i + 4] = (bf16)((float)v[i + 4] * inv * g1[i]);
+    }
+    st_bf16x8(yr + c * 8, o);
+  }
+}
+
+hipError_t launch_rmsnorm(const void* x, int64_t ldx, const float* gain, float eps, int M, int d,
+                          void* y, int64_t ldy, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  rmsnorm_kernel<<<M, 256, 0, s>>>((const bf16*)x, ldx, gain, eps, d, (bf16*)y, ldy);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ token -> (sequence, position)
+__device__ __forceinline__ void locate_token(int t, const int32_t* ctx_lens, const int32_t* cu_seqlens,
+                                             int n_seqs, int& seq, int& pos) {
+  if (ctx_lens) {  // decode: one token per request
+    seq = t;
+    pos = ctx_lens[t];
+  } else {         // prefill: largest s with cu_seqlens[s] <= t
+    int lo = 0, hi = n_seqs - 1;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (cu_seqlens[mid] <= t) lo = mid; else hi = mid - 1;
+    }
+    seq = lo;
+    pos = t - cu_seqlens[lo];
+  }
+}
+
+// ------------------------------------------------------------------ RoPE + KV append
+// One workgroup per token.  q heads are rotated in place; k heads are rotated and written to the
+// token's slot of the K pool; v heads are written (transposed) to the V pool.  Rotation pairs
+// channel i with channel i + head_dim/2 and turns the pair by pos * base^(-2i/head_dim); the
+// table holds (cos, sin) of that angle, computed in double precision on the host.
+__global__ __launch_bounds__(256) void rope_kv_kernel(bf16* __restrict__ qkv, int64_t ld, int n_q_heads,
+                                                      KvLayout kv, const float2* __restrict__ table,
+                                                      const int32_t* __restrict__ ctx_lens,
+                                                      const int32_t* __restrict__ cu_seqlens, int n_seqs,
+                                                      const int32_t* __restrict__ block_tables,
+                                                      int max_pages_per_seq) {
+  const int t = blockIdx.x;
+  int seq, pos;
+  locate_token(t, ctx_lens, cu_seqlens, n_seqs, seq, pos);
+  const int dh = kv.head_dim, half = dh >> 1;
+  const int page = block_tables[(int64_t)seq * max_pages_per_seq + pos / kv.page_size];
+  const int slot = pos % kv.page_size;
+  bf16* row = qkv + (int64_t)t * ld;
+  const float2* cs = table + (int64_t)pos * half;
+  const int per_head = half / 8;  // 16-byte units per half head
+  const int rot_heads = n_q_heads + kv.n_kv_heads;
+  bf16* kpool = (bf16*)kv.k_pool;
+  bf16* vpool = (bf16*)kv.v_pool;
+  for (int w = threadIdx.x; w < rot_heads * per_head; w += 256) {
+    const int head = w / per_head;
+    const int c0 = (w % per_head) * 8;
+    bf16* hp = row + (int64_t)head * dh;
+    const bf16x8 a = ld_bf16x8(hp + c0);
+    const bf16x8 b = ld_bf16x8(hp + half + c0);
+    bf16x8 ra, rb;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float2 t2 = cs[c0 + i];
+      const float fa = (float)a[i], fb = (float)b[i];
+      ra[i] = (bf16)(fa * t2.x - fb * t2.y);
+      rb[i] = (bf16)(fa * t2.y + fb * t2.x);
+    }
+    if (head < n_q_heads) {
+      st_bf16x8(hp + c0, ra);
+      st_bf16x8(hp + half + c0, rb);
+    } else {
+      const int kvh = head - n_q_heads;
+      bf16* dst = kpool + (((int64_t)page * kv.n_kv_heads + kvh) * kv.page_size + slot) * dh;
+      st_bf16x8(dst + c0, ra);
+      st_bf16x8(dst + half + c0, rb);
+    }
+  }
+  const bf16* vrow = row + (int64_t)(n_q_heads + kv.n_kv_heads) * dh;
+  for (int w = threadIdx.x; w < kv.n_kv_heads * dh; w += 256) {
+    const int kvh = w / dh, c = w % dh;
+    vpool[(((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot] = vrow[w];
+  }
+}
+
+hipError_t launch_rope_kv(void* qkv, int64_t ld, int n_tokens, int n_q_heads, const KvLayout& kv,
+                          const float2* rope_table, int max_pos, const int32_t* ctx_lens,
+                          const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
+                          int max_pages_per_seq, hipStream_t s) {
+  (void)max_pos;
+  if (n_tokens <= 0) return hipSuccess;
+  rope_kv_kernel<<<n_tokens, 256, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
+                                          n_seqs, block_tables, max_pages_per_seq);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ KV import / export
+__global__ __launch_bounds__(256) void kv_copy_kernel(int to_pages, bf16* __restrict__ k_packed,
+                                                      bf16* __restrict__ v_packed, KvLayout kv,
+                                                      const int32_t* __restrict__ cu_seqlens, int n_seqs,
+                                                      const int32_t* __restrict__ block_tables,
+                                                      int max_pages_per_seq) {
+  const int t = blockIdx.x;
+  int seq, pos;
+  locate_token(t, nullptr, cu_seqlens, n_seqs, seq, pos);
+  const int dh = kv.head_dim;
+  const int page = block_tables[(int64_t)seq * max_pages_per_seq + pos / kv.page_size];
+  const int slot = pos % kv.page_size;
+  bf16* kpool = (bf16*)kv.k_pool;
+  bf16* vpool = (bf16*)kv.v_pool;
+  for (int w = threadIdx.x; w < kv.n_kv_heads * dh; w += 256) {
+    const int kvh = w / dh, c = w % dh;
+    const int64_t ki = (((int64_t)page * kv.n_kv_heads + kvh) * kv.page_size + slot) * dh + c;
+    const int64_t vi = (((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot;
+    const int64_t pi = (int64_t)t * kv.n_kv_heads * dh + w;
+    if (to_pages) {
+      kpool[ki] = k_packed[pi];
+      vpool[vi] = v_packed[pi];
+    } else {
+      k_packed[pi] = kpool[ki];
+      v_packed[pi] = vpool[vi];
+    }
+  }
+}
+
+hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const KvLayout& kv,
+                          const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                          const int32_t* block_tables, int max_pages_per_seq, hipStream_t s) {
+  if (total_tokens <= 0) return hipSuccess;
+  kv_copy_kernel<<<total_tokens, 256, 0, s>>>(to_pages, (bf16*)k_packed, (bf16*)v_packed, kv, cu_seqlens,
+                                              n_seqs, block_tables, max_pages_per_seq);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ weight repack (one-time)
+// dst[row_of(n)][k] = bf16(src[k][n]) through a 32x32 LDS transpose.
+__global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ src, int src_is_f32,
+                                                     int64_t K, int64_t N, bf16* __restrict__ dst,
+                                                     int64_t dst_ld, int64_t row_off, int mode) {
+  __shared__ float tile[32][33];
+  const int64_t k0 = (int64_t)blockIdx.y * 32, n0 = (int64_t)blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int r = ty; r < 32; r += 8) {
+    const int64_t k = k0 + r, n = n0 + tx;
+    float v = 0.f;
+    if (k < K && n < N)
+      v = src_is_f32 ? ((const float*)src)[k * N + n] : (float)((const bf16*)src)[k * N + n];
+    tile[r][tx] = v;
+  }
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) {
+    const int64_t n = n0 + r, k = k0 + tx;
+    if (n < N && k < K) {
+      int64_t row;
+      if (mode == 0) row = row_off + n;
+      else row = (n / 32) * 64 + (n % 32) + (mode == 2 ? 32 : 0);
+      dst[row * dst_ld + k] = (bf16)tile[tx][r];
+    }
+  }
+}
+
+hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in, int64_t cols_out, void* dst,
+                         int64_t dst_ld, int64_t row_off, int mode, hipStream_t s) {
+  dim3 grid((unsigned)((cols_out + 31) / 32), (unsigned)((rows_in + 31) / 32));
+  repack_kernel<<<grid, 256, 0, s>>>(src, src_is_f32, rows_in, cols_out, (bf16*)dst, dst_ld, row_off, mode);
+  return hipGetLastError();
+}
+
+__global__ void convert_vec_kernel(const void* __restrict__ src, int src_is_f32, int64_t n,
+                                   float* __restrict__ dst) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src_is_f32 ? ((const float*)src)[i] : (float)((const bf16*)src)[i];
+}
+
+hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float* dst, hipStream_t s) {
+  convert_vec_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(src, src_is_f32, n, dst);
+  return hipGetLastError();
+}
+
+}  // namespace tdp

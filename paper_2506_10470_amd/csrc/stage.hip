@@ -1,0 +1,476 @@
+// C ABI of the stage library: configuration checks, memory ownership, weight repack and the
+// per-layer kernel sequence of the prefill and decode phases.  See include/tdp.h for the contract.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/tdp.h"
+#include "tdp_kernels.h"
+
+using namespace tdp;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+int fail_hip(hipError_t e, const char* what) {
+  g_err = std::string(what) + ": " + hipGetErrorString(e);
+  return e == hipErrorOutOfMemory ? TDP_ENOMEM : TDP_EHIP;
+}
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t e__ = (expr);                            \
+    if (e__ != hipSuccess) return fail_hip(e__, #expr); \
+  } while (0)
+
+int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+enum TimeClass { T_NORM = 0, T_QKV, T_ROPE, T_ATTN, T_O, T_GU, T_DOWN, T_COUNT };
+
+}  // namespace
+
+struct tdp_stage {
+  tdp_stage_config cfg;
+  int64_t dq, Nqkv, Nqkv_pad, d_pad, Fpad, Ngu_pad;
+  uint16_t *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wd = nullptr;  // bf16 bits
+  float *g_attn = nullptr, *g_mlp = nullptr;
+  uint16_t *kpool = nullptr, *vpool = nullptr;
+  int64_t pool_elems = 0;  // per layer, per pool
+  uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *h = nullptr, *u = nullptr, *xa = nullptr,
+           *xb = nullptr;
+  float* ws = nullptr;
+  int64_t ws_elems = 0;
+  float *part_o = nullptr, *part_ml = nullptr;
+  int max_chunks = 0;
+  float2* rope_table = nullptr;
+  int max_pos = 0;
+  int maxM = 0;
+  bool timing = false;
+  std::vector<hipEvent_t> ev_start, ev_stop;
+  std::vector<int> ev_class;
+  size_t ev_used = 0;
+};
+
+namespace {
+
+int check_config(const tdp_stage_config* c) {
+  if (!c) return fail(TDP_EINVAL, "config is null");
+  if (c->n_layers < 1) return fail(TDP_EINVAL, "n_layers must be >= 1");
+  if (c->d_model < 64 || c->d_model % 64) return fail(TDP_EINVAL, "d_model must be a positive multiple of 64");
+  if (c->head_dim != 64 && c->head_dim != 128) return fail(TDP_EINVAL, "head_dim must be 64 or 128");
+  if (c->n_kv_heads < 1 || c->n_q_heads < 1) return fail(TDP_EINVAL, "head counts must be >= 1");
+  if (c->n_q_heads % c->n_kv_heads) return fail(TDP_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+  if (c->n_q_heads / c->n_kv_heads > 16) return fail(TDP_EINVAL, "GQA group size above 16 is not supported");
+  if (c->d_ff < 4 || c->d_ff % 4) return fail(TDP_EINVAL, "d_ff must be a positive multiple of 4");
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(TDP_EINVAL, "rms_eps must be >= 0 and rope_base > 0");
+  if (c->page_size != 16) return fail(TDP_EINVAL, "page_size must be 16");
+  if (c->num_pages < 1) return fail(TDP_EINVAL, "num_pages must be >= 1");
+  if (c->max_batch < 0 || c->max_tokens < 0 || (c->max_batch == 0 && c->max_tokens == 0))
+    return fail(TDP_EINVAL, "max_batch / max_tokens must be >= 0 and not both 0");
+  if (c->max_seqs < 0 || (c->max_tokens > 0 && c->max_seqs < 1))
+    return fail(TDP_EINVAL, "max_seqs must be >= 1 when max_tokens > 0");
+  if (c->max_pages_per_seq < 1) return fail(TDP_EINVAL, "max_pages_per_seq must be >= 1");
+  if ((int64_t)c->max_pages_per_seq * 16 > (1 << 20)) return fail(TDP_EINVAL, "max_pages_per_seq too large");
+  return TDP_OK;
+}
+
+template <typename T>
+hipError_t dev_alloc(T** p, int64_t elems, bool zero) {
+  hipError_t e = hipMalloc((void**)p, (size_t)(elems > 0 ? elems : 1) * sizeof(T));
+  if (e != hipSuccess) return e;
+  if (zero) e = hipMemset(*p, 0, (size_t)(elems > 0 ? elems : 1) * sizeof(T));
+  return e;
+}
+
+struct Timer {
+  tdp_stage* st;
+  hipStream_t s;
+  bool on;
+  Timer(tdp_stage* st_, hipStream_t s_, int cls) : st(st_), s(s_), on(st_->timing) {
+    if (!on) return;
+    if (st->ev_used == st->ev_start.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+        on = false;
+        return;
+      }
+      st->ev_start.push_back(a);
+      st->ev_stop.push_back(b);
+      st->ev_class.push_back(cls);
+    }
+    st->ev_class[st->ev_used] = cls;
+    (void)hipEventRecord(st->ev_start[st->ev_used], s);
+  }
+  ~Timer() {
+    if (!on) return;
+    (void)hipEventRecord(st->ev_stop[st->ev_used], s);
+    st->ev_used++;
+  }
+};
+
+KvLayout kv_layout(tdp_stage* st, int layer) {
+  KvLayout kv;
+  kv.k_pool = st->kpool + (int64_t)layer * st->pool_elems;
+  kv.v_pool = st->vpool + (int64_t)layer * st->pool_elems;
+  kv.num_pages = st->cfg.num_pages;
+  kv.n_kv_heads = st->cfg.n_kv_heads;
+  kv.head_dim = st->cfg.head_dim;
+  kv.page_size = 16;
+  return kv;
+}
+
+// The layer sequence shared by both phases.  M tokens; decode when ctx_lens != null.
+int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, const int32_t* ctx_lens,
+               const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables, hipStream_t s) {
+  const tdp_stage_config& c = st->cfg;
+  const int64_t d = c.d_model;
+  st->ev_used = 0;
+  const uint16_t* x = (const uint16_t*)hidden_in;
+  int64_t ldx = d;
+  for (int l = 0; l < c.n_layers; ++l) {
+    const KvLayout kv = kv_layout(st, l);
+    uint16_t* x_next = (l == c.n_layers - 1) ? (uint16_t*)hidden_out : ((l & 1) ? st->xb : st->xa);
+    {  // a1: pre-attention RMSNorm
+      Timer t(st, s, T_NORM);
+      HIP_TRY(launch_rmsnorm(x, ldx, st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
+    }
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.workspace = st->ws;
+    g.workspace_elems = st->ws_elems;
+    g.M = M;
+    {  // a2: fused QKV projection
+      Timer t(st, s, T_QKV);
+      g.A = st->y; g.lda = d;
+      g.W = st->wqkv + (int64_t)l * st->Nqkv_pad * d; g.Kpad = d; g.Npad = st->Nqkv_pad;
+      g.N_store = (int)st->Nqkv_pad; g.out = st->qkv; g.ldo = st->Nqkv_pad;
+      g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {  // a3: rotary embedding + KV append
+      Timer t(st, s, T_ROPE);
+      HIP_TRY(launch_rope_kv(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, st->rope_table, st->max_pos, ctx_lens,
+                             cu_seqlens, n_seqs, block_tables, c.max_pages_per_seq, s));
+    }
+    {  // a4: attention
+      Timer t(st, s, T_ATTN);
+      if (ctx_lens)
+        HIP_TRY(launch_attn_decode(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, ctx_lens, block_tables,
+                                   c.max_pages_per_seq, st->part_o, st->part_ml, st->max_chunks, st->attn,
+                                   st->dq, s));
+      else
+        HIP_TRY(launch_attn_prefill(st->qkv, st->Nqkv_pad, M, n_seqs, c.n_q_heads, kv, cu_seqlens, block_tables,
+                                    c.max_pages_per_seq, st->attn, st->dq, s));
+    }
+    {  // a5: output projection + residual
+      Timer t(st, s, T_O);
+      g.A = st->attn; g.lda = st->dq;
+      g.W = st->wo + (int64_t)l * st->d_pad * st->dq; g.Kpad = st->dq; g.Npad = st->d_pad;
+      g.N_store = (int)d; g.out = st->h; g.ldo = d;
+      g.residual = x; g.ldr = ldx; g.epilogue = EPI_RESIDUAL;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {  // a6: pre-MLP RMSNorm
+      Timer t(st, s, T_NORM);
+      HIP_TRY(launch_rmsnorm(st->h, d, st->g_mlp + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
+    }
+    {  // a7: gate/up projection + SwiGLU
+      Timer t(st, s, T_GU);
+      g.A = st->y; g.lda = d;
+      g.W = st->wgu + (int64_t)l * st->Ngu_pad * d; g.Kpad = d; g.Npad = st->Ngu_pad;
+      g.N_store = (int)st->Fpad; g.out = st->u; g.ldo = st->Fpad;
+      g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_SWIGLU;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    {  // a8: down projection + residual
+      Timer t(st, s, T_DOWN);
+      g.A = st->u; g.lda = st->Fpad;
+      g.W = st->wd + (int64_t)l * st->d_pad * st->Fpad; g.Kpad = st->Fpad; g.Npad = st->d_pad;
+      g.N_store = (int)d; g.out = x_next; g.ldo = d;
+      g.residual = st->h; g.ldr = d; g.epilogue = EPI_RESIDUAL;
+      HIP_TRY(launch_gemm(g, s));
+    }
+    x = x_next;
+    ldx = d;
+  }
+  return TDP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tdp_abi_version(void) { return 1; }
+
+const char* tdp_last_error(void) { return g_err.c_str(); }
+
+int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
+  if (!out) return fail(TDP_EINVAL, "out is null");
+  int rc = check_config(cfg);
+  if (rc != TDP_OK) return rc;
+  tdp_stage* st = new (std::nothrow) tdp_stage();
+  if (!st) return fail(TDP_ENOMEM, "host allocation failed");
+  st->cfg = *cfg;
+  const tdp_stage_config& c = st->cfg;
+  const int64_t d = c.d_model, dh = c.head_dim, L = c.n_layers;
+  st->dq = (int64_t)c.n_q_heads * dh;
+  st->Nqkv = st->dq + 2 * (int64_t)c.n_kv_heads * dh;
+  st->Nqkv_pad = round_up(st->Nqkv, 256);
+  st->d_pad = round_up(d, 256);
+  st->Fpad = round_up(c.d_ff, 128);
+  st->Ngu_pad = 2 * st->Fpad;
+  st->maxM = c.max_batch > c.max_tokens ? c.max_batch : c.max_tokens;
+  st->pool_elems = (int64_t)c.num_pages * c.n_kv_heads * 16 * dh;
+  st->max_pos = c.max_pages_per_seq * 16;
+  st->max_chunks = (st->max_pos + kDecodeChunk - 1) / kDecodeChunk;
+
+  hipError_t e = gemm_setup();
+  auto A = [&](auto** p, int64_t n, bool zero) {
+    if (e == hipSuccess) e = dev_alloc(p, n, zero);
+  };
+  A(&st->wqkv, L * st->Nqkv_pad * d, true);
+  A(&st->wo, L * st->d_pad * st->dq, true);
+  A(&st->wgu, L * st->Ngu_pad * d, true);
+  A(&st->wd, L * st->d_pad * st->Fpad, true);
+  A(&st->g_attn, L * d, true);
+  A(&st->g_mlp, L * d, true);
+  A(&st->kpool, L * st->pool_elems, true);
+  A(&st->vpool, L * st->pool_elems, true);
+  const int64_t M = st->maxM;
+  A(&st->y, M * d, true);
+  A(&st->qkv, M * st->Nqkv_pad, true);
+  A(&st->attn, M * st->dq, true);
+  A(&st->h, M * d, true);
+  A(&st->u, M * st->Fpad, true);
+  A(&st->xa, M * d, true);
+  A(&st->xb, M * d, true);
+  {
+    int64_t maxN = st->Ngu_pad > st->Nqkv_pad ? st->Ngu_pad : st->Nqkv_pad;
+    if (st->d_pad > maxN) maxN = st->d_pad;
+    const int64_t mdec = M < 512 ? M : 512;
+    st->ws_elems = 8 * mdec * maxN;
+    if (st->ws_elems > (64ll << 20)) st->ws_elems = 64ll << 20;
+    A(&st->ws, st->ws_elems, false);
+  }
+  A(&st->part_o, (int64_t)c.max_batch * c.n_q_heads * st->max_chunks * dh, false);
+  A(&st->part_ml, (int64_t)c.max_batch * c.n_q_heads * st->max_chunks * 2, false);
+  A(&st->rope_table, (int64_t)st->max_pos * (dh / 2), false);
+  if (e == hipSuccess) {
+    // (cos, sin)(pos * base^(-2i/dh)) in double precision, stored as fp32
+    std::vector<float2> tab((size_t)st->max_pos * (dh / 2));
+    for (int64_t p = 0; p < st->max_pos; ++p)
+      for (int64_t i = 0; i < dh / 2; ++i) {
+        const double theta = pow((double)c.rope_base, -2.0 * (double)i / (double)dh);
+        const double ang = (double)p * theta;
+        tab[p * (dh / 2) + i] = make_float2((float)cos(ang), (float)sin(ang));
+      }
+    e = hipMemcpy(st->rope_table, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice);
+  }
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    int code = fail_hip(e, "tdp_stage_create");
+    tdp_stage_destroy(st);
+    return code;
+  }
+  *out = st;
+  return TDP_OK;
+}
+
+void tdp_stage_destroy(tdp_stage* st) {
+  if (!st) return;
+  (void)hipDeviceSynchronize();
+  void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->kpool, st->vpool, st->y,
+                  st->qkv, st->attn, st->h, st->u, st->xa, st->xb, st->ws, st->part_o, st->part_ml,
+                  st->rope_table};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  for (hipEvent_t ev : st->ev_start) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : st->ev_stop) (void)hipEventDestroy(ev);
+  delete st;
+}
+
+int tdp_stage_set_weight(tdp_stage* st, int32_t layer, int32_t which, const void* src, int32_t dtype,
+                         int32_t mem, int64_t rows, int64_t cols) {
+  if (!st || !src) return fail(TDP_EINVAL, "null stage or source");
+  const tdp_stage_config& c = st->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(TDP_EINVAL, "layer out of range");
+  if (dtype != TDP_F32 && dtype != TDP_BF16) return fail(TDP_EINVAL, "dtype must be TDP_F32 or TDP_BF16");
+  if (mem != TDP_HOST && mem != TDP_DEVICE) return fail(TDP_EINVAL, "mem must be TDP_HOST or TDP_DEVICE");
+  const int64_t d = c.d_model, dkv = (int64_t)c.n_kv_heads * c.head_dim, F = c.d_ff;
+  int64_t er = 0, ec = 0;
+  switch (which) {
+    case TDP_WQ: er = d; ec = st->dq; break;
+    case TDP_WK: case TDP_WV: er = d; ec = dkv; break;
+    case TDP_WO: er = st->dq; ec = d; break;
+    case TDP_WG: case TDP_WU: er = d; ec = F; break;
+    case TDP_WD: er = F; ec = d; break;
+    case TDP_G_ATTN: case TDP_G_MLP: er = d; ec = 1; break;
+    default: return fail(TDP_EINVAL, "unknown weight id");
+  }
+  if (rows != er || cols != ec) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "weight %d expects [%lld, %lld], got [%lld, %lld]", which, (long long)er,
+             (long long)ec, (long long)rows, (long long)cols);
+    return fail(TDP_EINVAL, buf);
+  }
+  const size_t esz = dtype == TDP_F32 ? 4 : 2;
+  const void* dsrc = src;
+  void* tmp = nullptr;
+  if (mem == TDP_HOST) {
+    HIP_TRY(hipMalloc(&tmp, (size_t)(rows * cols) * esz));
+    hipError_t e = hipMemcpy(tmp, src, (size_t)(rows * cols) * esz, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      (void)hipFree(tmp);
+      return fail_hip(e, "hipMemcpy(weight)");
+    }
+    dsrc = tmp;
+  }
+  const int f32 = dtype == TDP_F32;
+  hipError_t e = hipSuccess;
+  switch (which) {
+    case TDP_WQ:
+      e = launch_repack(dsrc, f32, rows, cols, st->wqkv + (int64_t)layer * st->Nqkv_pad * d, d, 0, 0, 0); break;
+    case TDP_WK:
+      e = launch_repack(dsrc, f32, rows, cols, st->wqkv + (int64_t)layer * st->Nqkv_pad * d, d, st->dq, 0, 0); break;
+    case TDP_WV:
+      e = launch_repack(dsrc, f32, rows, cols, st->wqkv + (int64_t)layer * st->Nqkv_pad * d, d, st->dq + dkv, 0, 0); break;
+    case TDP_WO:
+      e = launch_repack(dsrc, f32, rows, cols, st->wo + (int64_t)layer * st->d_pad * st->dq, st->dq, 0, 0, 0); break;
+    case TDP_WG:
+      e = launch_repack(dsrc, f32, rows, cols, st->wgu + (int64_t)layer * st->Ngu_pad * d, d, 0, 1, 0); break;
+    case TDP_WU:
+      e = launch_repack(dsrc, f32, rows, cols, st->wgu + (int64_t)layer * st->Ngu_pad * d, d, 0, 2, 0); break;
+    case TDP_WD:
+      e = launch_repack(dsrc, f32, rows, cols, st->wd + (int64_t)layer * st->d_pad * st->Fpad, st->Fpad, 0, 0, 0); break;
+    case TDP_G_ATTN:
+      e = launch_convert_vec(dsrc, f32, d, st->g_attn + (int64_t)layer * d, 0); break;
+    default:
+      e = launch_convert_vec(dsrc, f32, d, st->g_mlp + (int64_t)layer * d, 0); break;
+  }
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (tmp) (void)hipFree(tmp);
+  if (e != hipSuccess) return fail_hip(e, "weight repack");
+  return TDP_OK;
+}
+
+int tdp_stage_kv_pool(tdp_stage* st, int32_t layer, void** k_dev, void** v_dev, int64_t* bytes) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (layer < 0 || layer >= st->cfg.n_layers) return fail(TDP_EINVAL, "layer out of range");
+  if (k_dev) *k_dev = st->kpool + (int64_t)layer * st->pool_elems;
+  if (v_dev) *v_dev = st->vpool + (int64_t)layer * st->pool_elems;
+  if (bytes) *bytes = st->pool_elems * 2;
+  return TDP_OK;
+}
+
+static int kv_copy_common(int to_pages, tdp_stage* st, int32_t layer, void* k_packed, void* v_packed,
+                          const int32_t* cu_seqlens, const int32_t* block_tables, int32_t n_seqs,
+                          int32_t total_tokens, void* stream) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (layer < 0 || layer >= st->cfg.n_layers) return fail(TDP_EINVAL, "layer out of range");
+  if (n_seqs < 0 || total_tokens < 0) return fail(TDP_EINVAL, "negative size");
+  if (n_seqs == 0 || total_tokens == 0) return TDP_OK;
+  if (!k_packed || !v_packed || !cu_seqlens || !block_tables) return fail(TDP_EINVAL, "null pointer");
+  HIP_TRY(launch_kv_copy(to_pages, k_packed, v_packed, kv_layout(st, layer), cu_seqlens, n_seqs, total_tokens,
+                         block_tables, st->cfg.max_pages_per_seq, (hipStream_t)stream));
+  return TDP_OK;
+}
+
+int tdp_stage_kv_import(tdp_stage* st, int32_t layer, const void* k_packed, const void* v_packed,
+                        const int32_t* cu_seqlens, const int32_t* block_tables, int32_t n_seqs,
+                        int32_t total_tokens, void* stream) {
+  return kv_copy_common(1, st, layer, (void*)k_packed, (void*)v_packed, cu_seqlens, block_tables, n_seqs,
+                        total_tokens, stream);
+}
+
+int tdp_stage_kv_export(tdp_stage* st, int32_t layer, void* k_packed, void* v_packed,
+                        const int32_t* cu_seqlens, const int32_t* block_tables, int32_t n_seqs,
+                        int32_t total_tokens, void* stream) {
+  return kv_copy_common(0, st, layer, k_packed, v_packed, cu_seqlens, block_tables, n_seqs, total_tokens,
+                        stream);
+}
+
+int tdp_stage_prefill(tdp_stage* st, const void* hidden_in, const int32_t* cu_seqlens,
+                      const int32_t* block_tables, int32_t n_seqs, int32_t total_tokens, void* hidden_out,
+                      void* stream) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (n_seqs < 0 || total_tokens < 0) return fail(TDP_EINVAL, "negative size");
+  if (n_seqs > st->cfg.max_seqs) return fail(TDP_EINVAL, "n_seqs exceeds max_seqs");
+  if (total_tokens > st->cfg.max_tokens) return fail(TDP_EINVAL, "total_tokens exceeds max_tokens");
+  if (n_seqs == 0 || total_tokens == 0) return TDP_OK;
+  if (!hidden_in || !hidden_out || !cu_seqlens || !block_tables) return fail(TDP_EINVAL, "null pointer");
+  return run_layers(st, hidden_in, hidden_out, total_tokens, nullptr, cu_seqlens, n_seqs, block_tables,
+                    (hipStream_t)stream);
+}
+
+int tdp_stage_decode(tdp_stage* st, const void* hidden_in, const int32_t* ctx_lens, const int32_t* block_tables,
+                     int32_t batch, void* hidden_out, void* stream) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (batch < 0) return fail(TDP_EINVAL, "negative batch");
+  if (batch > st->cfg.max_batch) return fail(TDP_EINVAL, "batch exceeds max_batch");
+  if (batch == 0) return TDP_OK;
+  if (!hidden_in || !hidden_out || !ctx_lens || !block_tables) return fail(TDP_EINVAL, "null pointer");
+  return run_layers(st, hidden_in, hidden_out, batch, ctx_lens, nullptr, batch, block_tables,
+                    (hipStream_t)stream);
+}
+
+int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out, int32_t M, int32_t N, int32_t K,
+                  int32_t epilogue, int32_t tile, int32_t splits, void* stream) {
+  if (M < 0 || N <= 0 || K <= 0) return fail(TDP_EINVAL, "bad GEMM shape");
+  if (K % 64 || N % 4) return fail(TDP_EINVAL, "K must be a multiple of 64 and N of 4");
+  if (epilogue != 0 && epilogue != 1) return fail(TDP_EINVAL, "epilogue must be 0 or 1");
+  if (tile < 0 || tile > 4 || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
+  if (M == 0) return TDP_OK;
+  if (!A || !W || !out || (epilogue == 1 && !residual)) return fail(TDP_EINVAL, "null pointer");
+  hipStream_t s = (hipStream_t)stream;
+  HIP_TRY(gemm_setup());
+  const int64_t Npad = round_up(N, 256);
+  uint16_t* wt = nullptr;
+  float* ws = nullptr;
+  const int64_t ws_elems = (int64_t)(splits > 0 ? splits : 16) * M * Npad;
+  HIP_TRY(hipMalloc((void**)&wt, (size_t)(Npad * K) * 2));
+  hipError_t e = hipMalloc((void**)&ws, (size_t)ws_elems * 4);
+  if (e == hipSuccess) e = hipMemsetAsync(wt, 0, (size_t)(Npad * K) * 2, s);
+  if (e == hipSuccess) e = launch_repack(W, 0, K, N, wt, K, 0, 0, s);
+  if (e == hipSuccess) {
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = A; g.lda = K; g.W = wt; g.Kpad = K; g.Npad = Npad; g.M = M; g.N_store = N;
+    g.out = out; g.ldo = N; g.residual = residual; g.ldr = N;
+    g.epilogue = epilogue ? EPI_RESIDUAL : EPI_STORE;
+    g.workspace = ws; g.workspace_elems = ws_elems; g.force_tile = tile; g.force_splits = splits;
+    e = launch_gemm(g, s);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (wt) (void)hipFree(wt);
+  if (ws) (void)hipFree(ws);
+  if (e != hipSuccess) return fail_hip(e, "tdp_gemm_bf16");
+  return TDP_OK;
+}
+
+int tdp_stage_timing_enable(tdp_stage* st, int32_t on) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  st->timing = on != 0;
+  st->ev_used = 0;
+  return TDP_OK;
+}
+
+int tdp_stage_timing_read(tdp_stage* st, float* ms) {
+  if (!st || !ms) return fail(TDP_EINVAL, "null pointer");
+  for (int i = 0; i < T_COUNT; ++i) ms[i] = 0.f;
+  for (size_t i = 0; i < st->ev_used; ++i) {
+    HIP_TRY(hipEventSynchronize(st->ev_stop[i]));
+    float t = 0.f;
+    HIP_TRY(hipEventElapsedTime(&t, st->ev_start[i], st->ev_stop[i]));
+    ms[st->ev_class[i]] += t;
+  }
+  return TDP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Host-side launch interface of the HIP kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tdp {
+
+// ---- GEMM: out[M, N] = epilogue(A[M, K] * W^T), W stored [Npad][Kpad] (K contiguous) ---------
+enum Epilogue : int {
+  EPI_STORE = 0,     // out = acc                        (QKV projection)
+  EPI_RESIDUAL = 1,  // out = residual + acc             (O and down projections)
+  EPI_SWIGLU = 2,    // out[:, j] = silu(gate_j) * up_j  (gate/up projection; W rows interleaved
+                     //                                   in blocks of 32: gate block, up block)
+};
+
+struct GemmArgs {
+  const void* A;      // bf16 [M][lda]; rows >= M are never read
+  int64_t lda;
+  const void* W;      // bf16 [Npad][Kpad], zero padded
+  int64_t Kpad;       // multiple of 64
+  int64_t Npad;       // multiple of 256
+  int M;
+  int N_store;        // columns of `out` that exist (SWIGLU: Npad/2 is stored up to N_store)
+  void* out;          // bf16 [M][ldo]
+  int64_t ldo;
+  const void* residual;  // bf16 [M][ldr] or null
+  int64_t ldr;
+  int epilogue;
+  float* workspace;       // fp32 split-K partials
+  int64_t workspace_elems;
+  int force_tile;         // 0 = choose; else 1..4 selects a tile shape (tests / tuning)
+  int force_splits;       // 0 = choose
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+hipError_t gemm_setup();  // one-time function attributes (dynamic LDS size)
+
+// ---- weight repack: dst[row_of(n)][k] = src[k][n] -------------------------------------------
+// mode 0: row_of(n) = row_off + n;  mode 1: gate rows  (n/32)*64 + n%32;  mode 2: up rows (+32)
+hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in /*K*/, int64_t cols_out /*N*/,
+                         void* dst, int64_t dst_ld, int64_t row_off, int mode, hipStream_t s);
+hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float* dst, hipStream_t s);
+
+// ---- RMSNorm ---------------------------------------------------------------------------------
+hipError_t launch_rmsnorm(const void* x, int64_t ldx, const float* gain, float eps, int M, int d,
+                          void* y, int64_t ldy, hipStream_t s);
+
+// ---- RoPE + KV append ------------------------------------------------------------------------
+struct KvLayout {
+  void* k_pool;   // bf16 [num_pages][Hkv][page][dh]
+  void* v_pool;   // bf16 [num_pages][Hkv][dh][page]   (token index fastest)
+  int num_pages, n_kv_heads, head_dim, page_size;
+};
+// decode: token b sits at position ctx_lens[b] of sequence b.  prefill: token t of sequence s
+// (cu_seqlens[s] <= t < cu_seqlens[s+1]) sits at position t - cu_seqlens[s].
+hipError_t launch_rope_kv(void* qkv, int64_t ld, int n_tokens, int n_q_heads, const KvLayout& kv,
+                          const float2* rope_table, int max_pos, const int32_t* ctx_lens,
+                          const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
+                          int max_pages_per_seq, hipStream_t s);
+// KV import/export between packed logical order [tokens][Hkv][dh] and the paged pools.
+hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const KvLayout& kv,
+                          const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                          const int32_t* block_tables, int max_pages_per_seq, hipStream_t s);
+
+// ---- attention -------------------------------------------------------------------------------
+constexpr int kDecodeChunk = 256;  // tokens per split of the KV range
+hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
+                              const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq,
+                              float* part_o, float* part_ml, int max_chunks, void* out, int64_t ldo,
+                              hipStream_t s);
+hipError_t launch_attn_prefill(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
+                               const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
+                               int max_pages_per_seq, void* out, int64_t ldo, hipStream_t s);
+
+}  // namespace tdp

@@ -1,0 +1,64 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import os
+import re
+
+import pytest
+
+from paper_2506_10470_amd import tdp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def good_config(**kw):
+    base = dict(n_layers=2, d_model=256, n_q_heads=4, n_kv_heads=4, head_dim=64, d_ff=688, rms_eps=1e-5,
+                rope_base=10000.0, page_size=16, num_pages=8, max_batch=4, max_tokens=64, max_seqs=4,
+                max_pages_per_seq=4)
+    base.update(kw)
+    return tdp.StageConfig(**base)
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "tdp.h")).read()
+    declared = set(re.findall(r"TDP_API\s+[\w\s\*]+?\b(tdp_\w+)\s*\(", text))
+    assert len(declared) >= 12
+    for name in declared:
+        assert hasattr(tdp.lib, name), name
+        assert name in tdp._SIGS, "binding lacks " + name
+    assert tdp.tdp_abi_version() == 1
+
+
+@pytest.mark.parametrize("bad", [
+    dict(n_layers=0), dict(d_model=100), dict(head_dim=96), dict(n_q_heads=6, n_kv_heads=4),
+    dict(n_q_heads=34, n_kv_heads=2), dict(d_ff=0), dict(d_ff=690), dict(page_size=32), dict(num_pages=0),
+    dict(max_batch=0, max_tokens=0), dict(max_batch=-1), dict(max_pages_per_seq=0), dict(rope_base=0.0),
+    dict(max_tokens=8, max_seqs=0),
+])
+def test_create_rejects_bad_config_before_any_gpu_work(bad):
+    with pytest.raises(tdp.TdpError) as e:
+        tdp.tdp_stage_create(good_config(**bad))
+    assert e.value.code == tdp.EINVAL
+    assert tdp.last_error() != ""
+
+
+def test_null_arguments_are_einval():
+    import ctypes as C
+    assert tdp.lib.tdp_stage_create(None, None) == tdp.EINVAL
+    h = C.c_void_p()
+    assert tdp.lib.tdp_stage_create(None, C.byref(h)) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_decode(None, None, None, None, 1, None, None) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_prefill(None, None, None, None, 1, 1, None, None) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_kv_pool(None, 0, None, None, None) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_set_weight(None, 0, 0, None, 0, 0, 1, 1) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_timing_read(None, None) == tdp.EINVAL
+    tdp.lib.tdp_stage_destroy(None)          # allowed
+
+
+def test_gemm_entry_rejects_bad_shapes():
+    for M, N, K, epi, tile, splits in [(-1, 64, 64, 0, 0, 0), (1, 0, 64, 0, 0, 0), (1, 64, 100, 0, 0, 0),
+                                       (1, 66, 64, 0, 0, 0), (1, 64, 64, 2, 0, 0), (1, 64, 64, 0, 9, 0),
+                                       (1, 64, 64, 0, 0, -1)]:
+        assert tdp.lib.tdp_gemm_bf16(None, None, None, None, M, N, K, epi, tile, splits, None) == tdp.EINVAL
+    # M = 0 is a no-op, and null pointers with M > 0 are rejected
+    assert tdp.lib.tdp_gemm_bf16(None, None, None, None, 0, 64, 64, 0, 0, 0, None) == tdp.OK
+    assert tdp.lib.tdp_gemm_bf16(None, None, None, None, 1, 64, 64, 0, 0, 0, None) == tdp.EINVAL

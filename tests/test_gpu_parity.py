@@ -1,0 +1,313 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle on the same seeded
+inputs.  Outputs: max |gpu - oracle| / max |oracle row| <= 2e-2 (bf16 outputs, fp32 accumulation).
+KV slot addressing: bit-exact (every slot that must not change keeps its poison bits)."""
+import numpy as np
+import pytest
+import torch
+
+from harness import workload as W
+from oracle import stage_oracle as O
+from stage_helpers import TOL, Stage, f64, i32, oracle_layers, oracle_shape, row_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tdp():
+    from paper_2506_10470_amd import tdp as _tdp
+    return _tdp
+
+
+# ----------------------------------------------------------------------------- plumbing
+
+def test_generator_is_bit_identical_on_cpu_and_gpu():
+    sh = W.SHAPES["tiny"]
+    for name in ("wq", "wd", "g_mlp"):
+        a = W.weight(sh, 1, name, device="cpu")
+        b = W.weight(sh, 1, name, device="cuda").cpu()
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    a = W.kv_packed(sh, 0, "v", 100, 5, device="cpu", tok0=17, toks=9)
+    b = W.kv_packed(sh, 0, "v", 100, 5, device="cuda")[17:26].cpu()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def import_kv(tdp, st: Stage, lens: np.ndarray, tables: np.ndarray, stream_id: int):
+    """Fill the pages of sequences with generated K/V; returns per-sequence oracle caches."""
+    sh = st.shape
+    lens = np.asarray(lens, dtype=np.int64)
+    total = int(lens.sum())
+    cu = np.zeros(len(lens) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    caches = [[None] * sh.n_layers for _ in lens]
+    if total == 0:
+        for b in range(len(lens)):
+            for l in range(sh.n_layers):
+                caches[b][l] = (O.empty_cache(oracle_shape(sh)), O.empty_cache(oracle_shape(sh)))
+        return caches
+    cu_d, tab_d = i32(cu), i32(tables)
+    for l in range(sh.n_layers):
+        k = W.kv_packed(sh, l, "k", total, stream_id, device="cuda")
+        v = W.kv_packed(sh, l, "v", total, stream_id, device="cuda")
+        tdp.tdp_stage_kv_import(st.h, l, k, v, cu_d, tab_d, len(lens), total)
+        torch.cuda.synchronize()
+        kc, vc = f64(k), f64(v)
+        for b in range(len(lens)):
+            caches[b][l] = (kc[cu[b]:cu[b + 1]], vc[cu[b]:cu[b + 1]])
+    return caches
+
+
+def export_kv(tdp, st: Stage, lens: np.ndarray, tables: np.ndarray, layer: int):
+    sh = st.shape
+    total = int(np.sum(lens))
+    cu = np.zeros(len(lens) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    k = torch.empty(total, sh.n_kv_heads, sh.head_dim, dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    tdp.tdp_stage_kv_export(st.h, layer, k, v, i32(cu), i32(tables), len(lens), total)
+    torch.cuda.synchronize()
+    return f64(k), f64(v), cu
+
+
+def written_slot_mask(st: Stage, tables: np.ndarray, first: np.ndarray, last: np.ndarray):
+    """Boolean masks over the K and V pools of the slots positions first[b]..last[b]-1 occupy,
+    computed from the documented layout alone."""
+    sh = st.shape
+    mk = torch.zeros(st.num_pages, sh.n_kv_heads, 16, sh.head_dim, dtype=torch.bool)
+    mv = torch.zeros(st.num_pages, sh.n_kv_heads, sh.head_dim, 16, dtype=torch.bool)
+    for b in range(len(first)):
+        for p in range(int(first[b]), int(last[b])):
+            page, slot = int(tables[b, p // 16]), p % 16
+            mk[page, :, slot, :] = True
+            mv[page, :, :, slot] = True
+    return mk, mv
+
+
+def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_pages_per_seq=None):
+    sh = W.SHAPES[shape_name]
+    if n_layers:
+        sh = sh.with_layers(n_layers)
+    ctx_lens = np.asarray(ctx_lens, dtype=np.int64)
+    B = len(ctx_lens)
+    batch = W.make_decode_batch(ctx_lens, max_pages_per_seq=max_pages_per_seq)
+    with Stage(tdp, sh, batch.num_pages, B, 0, 0, batch.tables.shape[1]) as st:
+        st.poison()
+        caches = import_kv(tdp, st, ctx_lens, batch.tables, stream_id)
+        before = [tuple(t.clone() for t in st.pools(l)) for l in range(sh.n_layers)]
+        x = W.hidden_states(sh, B, stream_id, device="cuda")
+        out = torch.empty_like(x)
+        tdp.tdp_stage_decode(st.h, x, i32(batch.ctx_lens), i32(batch.tables), B, out)
+        torch.cuda.synchronize()
+        ref, new_caches = O.stage_decode(list(f64(x)), caches, list(oracle_layers(sh)), oracle_shape(sh))
+        err = row_rel_err(f64(out), np.stack(ref))
+        assert err <= TOL, err
+        # KV append: the new token's slot holds the oracle's K/V; every other bit is untouched
+        mk, mv = written_slot_mask(st, batch.tables, ctx_lens, ctx_lens + 1)
+        for l in range(sh.n_layers):
+            k_after, v_after = st.pools(l)
+            kb, vb = before[l]
+            same_k = (k_after.view(torch.int16) == kb.view(torch.int16)).cpu()
+            same_v = (v_after.view(torch.int16) == vb.view(torch.int16)).cpu()
+            assert bool(same_k[~mk].all()) and bool(same_v[~mv].all()), "a slot outside the append changed"
+            kx, vx, cu = export_kv(tdp, st, ctx_lens + 1, batch.tables, l)
+            for b in range(B):
+                k_ref, v_ref = new_caches[b][l]
+                assert row_rel_err(kx[cu[b + 1] - 1], k_ref[-1]) <= TOL
+                assert row_rel_err(vx[cu[b + 1] - 1], v_ref[-1]) <= TOL
+                # the pre-existing context reads back exactly as imported
+                assert np.array_equal(kx[cu[b]:cu[b + 1] - 1], k_ref[:-1])
+                assert np.array_equal(vx[cu[b]:cu[b + 1] - 1], v_ref[:-1])
+        return err
+
+
+def run_prefill_case(tdp, shape_name, seq_lens, n_layers=None, stream_id=2, decode_steps=0):
+    sh = W.SHAPES[shape_name]
+    if n_layers:
+        sh = sh.with_layers(n_layers)
+    seq_lens = np.asarray(seq_lens, dtype=np.int64)
+    n = len(seq_lens)
+    T = int(seq_lens.sum())
+    # reserve pages for the decode steps that follow
+    pb = W.make_prefill_batch(seq_lens + decode_steps)
+    cu = np.zeros(n + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(seq_lens)
+    with Stage(tdp, sh, pb.num_pages, n, T, n, pb.tables.shape[1]) as st:
+        st.poison()
+        x = W.hidden_states(sh, T, stream_id, device="cuda")
+        out = torch.empty_like(x)
+        tab_d = i32(pb.tables)
+        tdp.tdp_stage_prefill(st.h, x, i32(cu), tab_d, n, T, out)
+        torch.cuda.synchronize()
+        layers = list(oracle_layers(sh))
+        osh = oracle_shape(sh)
+        xs = f64(x)
+        ref, caches = O.stage_prefill([xs[cu[s]:cu[s + 1]] for s in range(n)], layers, osh)
+        err = row_rel_err(f64(out), np.concatenate(ref))
+        assert err <= TOL, err
+        mk, mv = written_slot_mask(st, pb.tables, np.zeros(n, dtype=np.int64), seq_lens)
+        for l in range(sh.n_layers):
+            k_pool, v_pool = st.pools(l)
+            # unwritten slots still hold the poison (NaN != NaN, so compare bits)
+            assert bool(torch.isnan(k_pool.cpu()[~mk]).all()) and bool(torch.isnan(v_pool.cpu()[~mv]).all())
+            assert not bool(torch.isnan(k_pool.cpu()[mk]).any()) and not bool(torch.isnan(v_pool.cpu()[mv]).any())
+            kx, vx, _ = export_kv(tdp, st, seq_lens, pb.tables, l)
+            for s in range(n):
+                assert row_rel_err(kx[cu[s]:cu[s + 1]].reshape(int(seq_lens[s]), -1),
+                                   caches[s][l][0].reshape(int(seq_lens[s]), -1)) <= TOL
+                assert row_rel_err(vx[cu[s]:cu[s + 1]].reshape(int(seq_lens[s]), -1),
+                                   caches[s][l][1].reshape(int(seq_lens[s]), -1)) <= TOL
+        # follow with decode steps on the cache the prefill produced (crosses page boundaries)
+        ctx = seq_lens.copy()
+        for step in range(decode_steps):
+            xd = W.hidden_states(sh, n, 100 + step, device="cuda")
+            od = torch.empty_like(xd)
+            tdp.tdp_stage_decode(st.h, xd, i32(ctx), tab_d, n, od)
+            torch.cuda.synchronize()
+            refd, caches = O.stage_decode(list(f64(xd)), caches, layers, osh)
+            e2 = row_rel_err(f64(od), np.stack(refd))
+            assert e2 <= TOL, (step, e2)
+            err = max(err, e2)
+            ctx = ctx + 1
+        return err
+
+
+# ----------------------------------------------------------------------------- GEMM alone
+
+@pytest.mark.parametrize("M,N,K,tile,splits,epi", [
+    (4, 768, 256, 0, 0, 0), (4, 256, 704, 0, 0, 1), (33, 320, 128, 4, 2, 0), (64, 512, 512, 3, 1, 1),
+    (100, 384, 256, 2, 3, 0), (130, 1024, 320, 2, 1, 1), (300, 768, 1024, 1, 1, 0), (257, 516, 192, 1, 2, 1),
+    (512, 1280, 2048, 0, 0, 0), (1000, 256, 64, 0, 0, 1),
+])
+def test_gemm_matches_fp64_product(tdp, M, N, K, tile, splits, epi):
+    g = torch.Generator(device="cpu").manual_seed(M * 131 + N)
+    A = torch.randn(M, K, generator=g).to(torch.bfloat16).cuda()
+    Wm = (torch.randn(K, N, generator=g) * 0.05).to(torch.bfloat16).cuda()
+    R = torch.randn(M, N, generator=g).to(torch.bfloat16).cuda()
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    tdp.tdp_gemm_bf16(A, Wm, R if epi else None, out, M, N, K, epi, tile, splits)
+    ref = f64(A) @ f64(Wm) + (f64(R) if epi else 0.0)
+    assert row_rel_err(f64(out), ref) <= 1e-2
+
+
+# ----------------------------------------------------------------------------- the stage
+
+def test_decode_tiny_config(tdp):
+    """Benchmark configuration 0: batch 4, contexts uniform in [16, 64], random block tables."""
+    run_decode_case(tdp, "tiny", W.decode_ctx_lens("tiny", 4))
+
+
+def test_prefill_tiny_config(tdp):
+    """Benchmark configuration 0: 4 prompts, lengths uniform in [8, 32]."""
+    run_prefill_case(tdp, "tiny", W.prefill_seq_lens("tiny", 4))
+
+
+@pytest.mark.parametrize("shape", ["tiny", "tiny_gqa", "tiny_h128"])
+def test_prefill_then_decode_across_page_boundaries(tdp, shape):
+    run_prefill_case(tdp, shape, [1, 15, 16, 17, 33, 70], decode_steps=3)
+
+
+@pytest.mark.parametrize("shape", ["tiny_gqa", "tiny_h128"])
+def test_decode_edge_contexts(tdp, shape):
+    """ctx = 0 (attention over the token itself), page edges, split edges (256 tokens per split)."""
+    run_decode_case(tdp, shape, [0, 1, 15, 16, 31, 32, 255, 256, 257, 511, 512, 700])
+
+
+def test_decode_is_invariant_under_block_table_permutation(tdp):
+    sh = W.SHAPES["tiny_gqa"]
+    ctx = np.array([5, 40, 300, 77], dtype=np.int64)
+    outs = []
+    for seed in (1, 2):
+        batch = W.make_decode_batch(ctx, seed=seed)
+        with Stage(tdp, sh, batch.num_pages, 4, 0, 0, batch.tables.shape[1]) as st:
+            st.poison()
+            import_kv(tdp, st, ctx, batch.tables, 9)
+            x = W.hidden_states(sh, 4, 9, device="cuda")
+            out = torch.empty_like(x)
+            tdp.tdp_stage_decode(st.h, x, i32(ctx), i32(batch.tables), 4, out)
+            torch.cuda.synchronize()
+            outs.append(out.view(torch.int16).cpu())
+    assert torch.equal(outs[0], outs[1])
+
+
+def test_requests_are_independent_on_the_gpu(tdp):
+    """A request's output does not depend on the rest of the batch: bit-identical alone / in a batch
+    is not promised (tile shapes differ), the tolerance is."""
+    sh = W.SHAPES["tiny"]
+    ctx = np.array([20, 33, 64], dtype=np.int64)
+    batch = W.make_decode_batch(ctx)
+    with Stage(tdp, sh, batch.num_pages, 3, 0, 0, batch.tables.shape[1]) as st:
+        import_kv(tdp, st, ctx, batch.tables, 4)
+        x = W.hidden_states(sh, 3, 4, device="cuda")
+        out = torch.empty_like(x)
+        tdp.tdp_stage_decode(st.h, x, i32(ctx), i32(batch.tables), 3, out)
+        solo = torch.empty_like(x[1:2])
+        tdp.tdp_stage_decode(st.h, x[1:2].contiguous(), i32(ctx[1:2]), i32(batch.tables[1:2]), 1, solo)
+        torch.cuda.synchronize()
+        assert row_rel_err(f64(solo), f64(out[1:2])) <= 1e-2
+
+
+def test_empty_batches_are_no_ops_and_limits_are_enforced(tdp):
+    sh = W.SHAPES["tiny"]
+    with Stage(tdp, sh, 8, 4, 64, 4, 4, load_weights=False) as st:
+        tdp.tdp_stage_decode(st.h, None, None, None, 0, None)
+        tdp.tdp_stage_prefill(st.h, None, None, None, 0, 0, None)
+        x = torch.zeros(8, sh.d_model, dtype=torch.bfloat16, device="cuda")
+        with pytest.raises(tdp.TdpError) as e:
+            tdp.tdp_stage_decode(st.h, x, i32([1] * 5), i32(np.zeros((5, 4))), 5, x)
+        assert e.value.code == tdp.EINVAL
+        with pytest.raises(tdp.TdpError):
+            tdp.tdp_stage_prefill(st.h, x, i32([0, 65]), i32(np.zeros((1, 4))), 1, 65, x)
+        with pytest.raises(tdp.TdpError):
+            tdp.tdp_stage_set_weight(st.h, 0, tdp.WQ, x, tdp.BF16, tdp.DEVICE, 3, 3)
+
+
+def test_fp32_and_host_weights_are_rounded_like_bf16_weights(tdp):
+    sh = W.SHAPES["tiny"]
+    ctx = np.array([16, 40], dtype=np.int64)
+    batch = W.make_decode_batch(ctx)
+    outs = []
+    for mode in ("bf16_dev", "f32_host"):
+        with Stage(tdp, sh, batch.num_pages, 2, 0, 0, batch.tables.shape[1], load_weights=False) as st:
+            if mode == "bf16_dev":
+                # fp32 source rounded to bf16 by torch, handed over on the device
+                for l in range(sh.n_layers):
+                    for name in W.WEIGHT_NAMES:
+                        w = W.weight(sh, l, name, device="cuda", dtype=torch.float32).to(torch.bfloat16).contiguous()
+                        tdp.tdp_stage_set_weight(st.h, l, tdp.WEIGHT_IDS[name], w, tdp.BF16, tdp.DEVICE,
+                                                 w.shape[0], w.shape[1] if w.dim() == 2 else 1)
+            else:
+                for l in range(sh.n_layers):
+                    for name in W.WEIGHT_NAMES:
+                        w = W.weight(sh, l, name, device="cpu", dtype=torch.float32)
+                        if name.startswith("g_"):
+                            w = w.to(torch.bfloat16).to(torch.float32)   # same gains in both runs
+                        w = w.contiguous()
+                        tdp.tdp_stage_set_weight(st.h, l, tdp.WEIGHT_IDS[name], w, tdp.F32, tdp.HOST,
+                                                 w.shape[0], w.shape[1] if w.dim() == 2 else 1)
+            import_kv(tdp, st, ctx, batch.tables, 6)
+            x = W.hidden_states(sh, 2, 6, device="cuda")
+            out = torch.empty_like(x)
+            tdp.tdp_stage_decode(st.h, x, i32(ctx), i32(batch.tables), 2, out)
+            torch.cuda.synchronize()
+            outs.append(out.view(torch.int16).cpu())
+    assert torch.equal(outs[0], outs[1])
+
+
+# ----------------------------------------------------------------------------- several tiles, ragged tails
+
+def test_decode_13b_shaped_layer_many_tiles(tdp):
+    """One 13B-shaped layer: 40 heads x 128, FFN 13824; batch 40 with contexts up to ~900 tokens
+    (several KV splits, ragged last pages, ragged M tile)."""
+    ctx = W.decode_ctx_lens("13b_quarter", 40)
+    ctx = np.minimum(ctx, 900)
+    run_decode_case(tdp, "13b_quarter", ctx, n_layers=1)
+
+
+def test_prefill_7b_shaped_layer_many_tiles(tdp):
+    """One 7B-shaped layer, 5 prompts of ragged length (total 527 tokens: three M tiles)."""
+    run_prefill_case(tdp, "7b_quarter", [200, 31, 129, 64, 103], n_layers=1)
+
+
+def test_decode_70b_shaped_layer_gqa(tdp):
+    """One 70B-shaped layer (64 query heads on 8 KV heads), batch 24."""
+    ctx = np.minimum(W.decode_ctx_lens("70b_quarter", 24), 700)
+    run_decode_case(tdp, "70b_quarter", ctx, n_layers=1)
