@@ -1,0 +1,295 @@
+#!/usr/bin/env python3
+"""Benchmark of the pipeline-stage forward pass on one MI355X.
+
+A "step" is one decode step of the whole stage (every layer: RMSNorm, QKV GEMM, RoPE + KV append,
+paged attention, O GEMM, RMSNorm, gate/up GEMM + SwiGLU, down GEMM) over one synthetic batch whose
+weights, hidden states, block tables and KV cache are resident in HBM before the timed region.
+The default workload is the 70B-shaped quarter stage (20 layers, GQA 64/8, FFN 28672, bf16) at
+decode batch 512; the same run also reports the decode batch-size sweep (the computational-
+intensity curve the paper's phase-switch decision is built on, Sec. 3.5) and the prefill rate.
+
+Prints ONE JSON line.  Only one GPU is used; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32):
+    """One stage sized for the decode batch and the prefill batch, page ranges disjoint."""
+    import torch
+    max_pps = 4096 // 16 + 1
+    dec = W.make_decode_batch(dec_ctx, max_pages_per_seq=max_pps)
+    pre = W.make_prefill_batch(pre_lens, max_pages_per_seq=max_pps)
+    pre_tables = np.where(pre.tables >= 0, pre.tables + dec.num_pages, -1).astype(np.int32)
+    t0 = time.time()
+    st = Stage(tdp, shape, dec.num_pages + pre.num_pages, len(dec_ctx), int(pre_lens.sum()), len(pre_lens),
+               max_pps, load_weights=True)
+    torch.cuda.synchronize()
+    log("stage created, weights loaded: %.1f s" % (time.time() - t0))
+    # pre-existing KV ~ N(0,1), written through the library's import kernel
+    t0 = time.time()
+    total = int(dec_ctx.sum())
+    cu = np.zeros(len(dec_ctx) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(dec_ctx)
+    cu_d, tab_d = i32(cu), i32(dec.tables)
+    for l in range(shape.n_layers):
+        k = W.kv_packed(shape, l, "k", total, 1, device="cuda")
+        v = W.kv_packed(shape, l, "v", total, 1, device="cuda")
+        tdp.tdp_stage_kv_import(st.h, l, k, v, cu_d, tab_d, len(dec_ctx), total)
+        torch.cuda.synchronize()
+        del k, v
+    log("KV cache filled (%d tokens x %d layers): %.1f s" % (total, shape.n_layers, time.time() - t0))
+    return st, dec, pre, pre_tables, cu
+
+
+def time_calls(fn, warmup, steps):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def class_times(tdp, st, fn, reps):
+    """Average milliseconds per call and kernel class, from HIP events on the launch stream."""
+    import torch
+    tdp.tdp_stage_timing_enable(st.h, True)
+    fn()
+    torch.cuda.synchronize()
+    acc = {}
+    for _ in range(reps):
+        fn()
+        t = tdp.tdp_stage_timing_read(st.h)
+        for k, v in t.items():
+            acc[k] = acc.get(k, 0.0) + v / reps
+    tdp.tdp_stage_timing_enable(st.h, False)
+    return acc
+
+
+def kernel_rooflines(shape, M, kv_read_bytes, attn_flops, times_ms, phase):
+    """Per kernel class: algorithmic bytes and flops per stage pass, the roofline that binds it
+    (HBM when flops/byte is below peak_flops/peak_bytes, else MFMA), achieved rate and fraction."""
+    d, dq, dkv, F, L = shape.d_model, shape.d_q, shape.d_kv, shape.d_ff, shape.n_layers
+    gemms = {"gemm_qkv": (dq + 2 * dkv, d), "gemm_o": (d, dq), "gemm_gate_up": (2 * F, d), "gemm_down": (d, F)}
+    ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    out = {}
+    for name, (N, K) in gemms.items():
+        byts = L * N * K * 2
+        flops = 2 * M * L * N * K
+        out[name] = (byts, flops)
+    out["attention"] = (kv_read_bytes, attn_flops)
+    res = {}
+    for name, (byts, flops) in out.items():
+        ms = times_ms.get(name, 0.0)
+        if ms <= 0:
+            continue
+        launches = L
+        bound = "mfma" if (phase == "prefill" or flops / byts > ridge) else "hbm"
+        if bound == "hbm":
+            ach, peak, unit = byts / (ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = flops / (ms * 1e-3) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        res[name] = {"bound": bound, "achieved": round(ach, 1), "peak": peak, "unit": unit,
+                     "frac": round(ach / peak, 4), "avg_launch_ms": round(ms / launches, 4),
+                     "launches_per_step": launches, "alg_bytes_per_launch": byts // launches,
+                     "alg_flops_per_launch": flops // launches, "traffic": None}
+    return res
+
+
+def cpu_baseline(shape, dec_ctx, cu, budget_layers=4, n_requests=64):
+    """The fp64 oracle, as it stands, on a bounded sample of the decode workload: `n_requests`
+    requests spread evenly over the batch sorted by context length (shortest and longest included)
+    through the first `budget_layers` layers, scaled to the full layer count.  Weight generation /
+    widening to fp64 is input preparation and is not timed."""
+    import torch
+    from threadpoolctl import threadpool_info
+    from harness import workload as W
+    from oracle import stage_oracle as O
+    order = np.argsort(dec_ctx, kind="stable")
+    budget_layers = min(budget_layers, shape.n_layers)
+    picks = np.unique(np.linspace(0, len(order) - 1, min(n_requests, len(order))).round().astype(int))
+    sample = [int(order[i]) for i in picks]
+    osh = O.Shape(shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.rms_eps, shape.rope_base)
+    t_prep = time.time()
+    layers = []
+    for l in range(budget_layers):
+        ws = []
+        for name in W.WEIGHT_NAMES:
+            w = W.weight(shape, l, name, device="cuda")
+            if not name.startswith("g_"):
+                w = w.to(torch.bfloat16)
+            ws.append(w.cpu().to(torch.float64).numpy())
+        layers.append(O.LayerWeights(*ws))
+    total = int(dec_ctx.sum())
+    caches = []
+    for b in sample:
+        c = []
+        for l in range(budget_layers):
+            k = W.kv_packed(shape, l, "k", total, 1, device="cuda", tok0=int(cu[b]), toks=int(dec_ctx[b]))
+            v = W.kv_packed(shape, l, "v", total, 1, device="cuda", tok0=int(cu[b]), toks=int(dec_ctx[b]))
+            c.append((k.cpu().to(torch.float64).numpy(), v.cpu().to(torch.float64).numpy()))
+        caches.append(c)
+    x = W.hidden_states(shape, len(dec_ctx), 1, device="cuda").cpu().to(torch.float64).numpy()
+    t_prep = time.time() - t_prep
+    t0 = time.perf_counter()
+    O.stage_decode([x[b] for b in sample], caches, layers, osh)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    tok_s = len(sample) / (dt * shape.n_layers / budget_layers)
+    return {"value": round(tok_s, 4), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "decode: %d requests (ctx %d..%d, mean %.0f) x %d of %d layers, %.1f s timed, scaled by "
+                      "layers; input preparation %.1f s not timed" % (
+                          len(sample), min(int(dec_ctx[b]) for b in sample), max(int(dec_ctx[b]) for b in sample),
+                          float(np.mean([dec_ctx[b] for b in sample])), budget_layers, shape.n_layers, dt, t_prep)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="70b_quarter", choices=["70b_quarter", "13b_quarter", "7b_quarter"])
+    ap.add_argument("--batch", type=int, default=512)
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only)")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (pipeline stages would each run "
+              "this same code on their own GPU); re-run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from harness import workload as W
+    from harness.runner import Stage, i32
+    from paper_2506_10470_amd import accounting as A
+    from paper_2506_10470_amd import tdp
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    shape = W.SHAPES[args.workload]
+    if args.layers:
+        shape = shape.with_layers(args.layers)
+    B = args.batch
+    n_prompts = {"70b_quarter": 16, "13b_quarter": 32, "7b_quarter": 32}[args.workload]
+    dec_ctx = W.decode_ctx_lens(args.workload, B)
+    pre_lens = W.prefill_seq_lens(args.workload, n_prompts)
+    st, dec, pre, pre_tables, cu = build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32)
+    stream = torch.cuda.current_stream()
+    sargs = (shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff)
+
+    x = W.hidden_states(shape, B, 1, device="cuda")
+    out = torch.empty_like(x)
+    ctx_d, tab_d = i32(dec.ctx_lens), i32(dec.tables)
+
+    def decode_fn(b=B):
+        tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, b, out, stream)
+
+    # ---- headline: decode at the full batch
+    ms = time_calls(decode_fn, args.warmup, args.steps)
+    work = A.decode_step_work(*sargs, dec_ctx)
+    log("decode B=%d: %.3f ms/step, %.0f tok/s, %.0f GB/s algorithmic" % (B, ms, B / ms * 1e3,
+                                                                          work["bytes"] / ms / 1e6))
+    ct = class_times(tdp, st, decode_fn, 5)
+    kern = kernel_rooflines(shape, B, work["kv_read_bytes"], work["attn_flops"], ct, "decode")
+    dominant = max(kern, key=lambda k: ct[k])
+    roof = dict(kern[dominant])
+    roof["kernel"] = dominant
+    t_min = sum(max(v["alg_bytes_per_launch"] * v["launches_per_step"] / (HBM_PEAK_GBS * 1e9),
+                    v["alg_flops_per_launch"] * v["launches_per_step"] / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+                for v in kern.values()) * 1e3
+
+    result = {
+        "metric": "stage decode tok/s vs batch; prefill tok/s; % of HBM / MFMA roofline",
+        "value": round(B / ms * 1e3, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s stage, decode phase, batch %d" % (args.workload, B),
+                   "n_layers": shape.n_layers, "d_model": shape.d_model, "n_q_heads": shape.n_q_heads,
+                   "n_kv_heads": shape.n_kv_heads, "head_dim": shape.head_dim, "d_ff": shape.d_ff,
+                   "batch": B, "mean_ctx": round(float(dec_ctx.mean()), 1), "max_ctx": int(dec_ctx.max()),
+                   "page_size": 16, "parallelism": "single GPU"},
+        "roofline": roof,
+        "decode": {"alg_bytes_per_step": work["bytes"], "alg_flops_per_step": work["flops"],
+                   "hbm_gbs": round(work["bytes"] / ms / 1e6, 1),
+                   "hbm_frac": round(work["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
+                   "composite_t_min_ms": round(t_min, 3), "composite_frac": round(t_min / ms, 4),
+                   "class_ms": {k: round(v, 4) for k, v in ct.items()}, "kernels": kern},
+    }
+
+    # ---- decode batch-size sweep on the same stage (first b requests of the batch)
+    if not args.no_sweep:
+        sweep = []
+        for b in (16, 32, 64, 128, 256, 512):
+            if b > B:
+                continue
+            msb = time_calls(lambda: decode_fn(b), 3, 10)
+            wb = A.decode_step_work(*sargs, dec_ctx[:b])
+            sweep.append({"batch": b, "ms_per_step": round(msb, 4), "tok_s": round(b / msb * 1e3, 1),
+                          "hbm_gbs": round(wb["bytes"] / msb / 1e6, 1),
+                          "hbm_frac": round(wb["bytes"] / msb / 1e6 / HBM_PEAK_GBS, 4)})
+            log("  sweep B=%d: %.3f ms, %.0f tok/s, %.0f GB/s" % (b, msb, b / msb * 1e3, wb["bytes"] / msb / 1e6))
+        peak = max(s["tok_s"] for s in sweep)
+        for s in sweep:
+            s["spatial_intensity"] = round(s["tok_s"] / peak, 4)     # Achieved / Peak (paper Eq. 1)
+        result["decode_sweep"] = sweep
+
+    # ---- prefill
+    if not args.no_prefill:
+        T = int(pre_lens.sum())
+        xp = W.hidden_states(shape, T, 2, device="cuda")
+        op = torch.empty_like(xp)
+        cu_p, tab_p = i32(pre.cu_seqlens), i32(pre_tables)
+
+        def prefill_fn():
+            tdp.tdp_stage_prefill(st.h, xp, cu_p, tab_p, len(pre_lens), T, op, stream)
+
+        msp = time_calls(prefill_fn, 1, 3)
+        wp = A.prefill_work(*sargs, pre_lens)
+        ctp = class_times(tdp, st, prefill_fn, 2)
+        kp = kernel_rooflines(shape, T, 0, wp["attn_flops"], {k: v for k, v in ctp.items()}, "prefill")
+        gemm_ms = sum(ctp[k] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down"))
+        result["prefill"] = {"tokens": T, "n_prompts": len(pre_lens), "ms": round(msp, 3),
+                             "tok_s": round(T / msp * 1e3, 1),
+                             "tflops": round(wp["flops"] / msp / 1e9, 1),
+                             "mfma_frac": round(wp["flops"] / msp / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                             "gemm_tflops": round(wp["gemm_flops"] / gemm_ms / 1e9, 1),
+                             "gemm_mfma_frac": round(wp["gemm_flops"] / gemm_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                             "class_ms": {k: round(v, 3) for k, v in ctp.items()}, "kernels": kp}
+        log("prefill T=%d: %.1f ms, %.0f tok/s, %.0f TFLOP/s (GEMMs %.0f TFLOP/s)" % (
+            T, msp, T / msp * 1e3, wp["flops"] / msp / 1e9, wp["gemm_flops"] / gemm_ms / 1e9))
+        del xp, op
+
+    st.close()
+    torch.cuda.empty_cache()
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(shape, dec_ctx, cu)
+        log("cpu oracle: %s tok/s (%s)" % (result["cpu_baseline"]["value"], result["cpu_baseline"]["sample"]))
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

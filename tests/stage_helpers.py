@@ -1,81 +1,15 @@
-"""Shared plumbing of the GPU parity tests: build a stage from generated weights, view the KV
-pools as tensors, turn generated weights into oracle inputs, compare with the stated tolerance.
-No arithmetic of the method lives here."""
+"""Oracle-side plumbing of the GPU parity tests: turn generated weights into oracle inputs and
+compare with the stated tolerance.  No arithmetic of the method lives here."""
 from __future__ import annotations
 
 import numpy as np
 import torch
 
 from harness import workload as W
+from harness.runner import Stage, dev_view_bf16, i32  # noqa: F401  (re-exported for the tests)
 from oracle import stage_oracle as O
 
 TOL = 2e-2          # max |gpu - oracle| / max |oracle row|, on bf16 outputs with fp32 accumulation
-
-
-class DevMem:
-    """Zero-copy view of raw device memory through the CUDA array interface."""
-
-    def __init__(self, ptr: int, n_elems: int, typestr: str = "<i2"):
-        self.__cuda_array_interface__ = {"shape": (n_elems,), "typestr": typestr,
-                                         "data": (ptr, False), "version": 2}
-
-
-def dev_view_bf16(ptr: int, nbytes: int) -> torch.Tensor:
-    return torch.as_tensor(DevMem(ptr, nbytes // 2), device="cuda").view(torch.bfloat16)
-
-
-class Stage:
-    def __init__(self, tdp, shape: W.StageShape, num_pages: int, max_batch: int, max_tokens: int,
-                 max_seqs: int, max_pages_per_seq: int, weight_dtype=torch.bfloat16, load_weights=True):
-        self.tdp = tdp
-        self.shape = shape
-        self.cfg = tdp.StageConfig(
-            n_layers=shape.n_layers, d_model=shape.d_model, n_q_heads=shape.n_q_heads,
-            n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, d_ff=shape.d_ff, rms_eps=shape.rms_eps,
-            rope_base=shape.rope_base, page_size=shape.page_size, num_pages=num_pages, max_batch=max_batch,
-            max_tokens=max_tokens, max_seqs=max_seqs, max_pages_per_seq=max_pages_per_seq)
-        self.h = tdp.tdp_stage_create(self.cfg)
-        self.num_pages = num_pages
-        self.max_pages_per_seq = max_pages_per_seq
-        if load_weights:
-            self.load_weights(weight_dtype)
-
-    def load_weights(self, dtype=torch.bfloat16):
-        tdp, sh = self.tdp, self.shape
-        for l in range(sh.n_layers):
-            for name in W.WEIGHT_NAMES:
-                w = W.weight(sh, l, name, device="cuda", dtype=dtype).contiguous()
-                rows = w.shape[0]
-                cols = w.shape[1] if w.dim() == 2 else 1
-                tdp.tdp_stage_set_weight(self.h, l, tdp.WEIGHT_IDS[name], w,
-                                         tdp.BF16 if dtype == torch.bfloat16 else tdp.F32, tdp.DEVICE, rows, cols)
-                del w
-
-    def pools(self, layer):
-        """(K [pages, Hkv, 16, dh], V [pages, Hkv, dh, 16]) zero-copy bf16 views."""
-        k, v, n = self.tdp.tdp_stage_kv_pool(self.h, layer)
-        sh = self.shape
-        kt = dev_view_bf16(k, n).view(self.num_pages, sh.n_kv_heads, 16, sh.head_dim)
-        vt = dev_view_bf16(v, n).view(self.num_pages, sh.n_kv_heads, sh.head_dim, 16)
-        return kt, vt
-
-    def poison(self):
-        for l in range(self.shape.n_layers):
-            k, v = self.pools(l)
-            k.fill_(float("nan"))
-            v.fill_(float("nan"))
-        torch.cuda.synchronize()
-
-    def close(self):
-        if self.h:
-            self.tdp.tdp_stage_destroy(self.h)
-            self.h = None
-
-    def __enter__(self):
-        return self
-
-    def __exit__(self, *a):
-        self.close()
 
 
 def oracle_shape(sh: W.StageShape) -> O.Shape:
@@ -116,7 +50,3 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     denom = np.max(np.abs(ref), axis=-1)
     denom = np.where(denom == 0, 1.0, denom)
     return float(np.max(np.max(np.abs(got - ref), axis=-1) / denom))
-
-
-def i32(a, device="cuda") -> torch.Tensor:
-    return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device=device)
