@@ -12,6 +12,9 @@
 // swizzle of the 16-byte chunks so that both the staging writes and the fragment reads are free
 // of bank conflicts.  For small M (decode) the K range is split across workgroups and fp32
 // partials are reduced by a second kernel that applies the epilogue.
+#include <stdio.h>
+#include <stdlib.h>
+
 #include "tdp_device.h"
 #include "tdp_kernels.h"
 
@@ -27,9 +30,229 @@ struct GemmParams {
   int M, N_store, epilogue;
   int k_tiles_total, k_tiles_per_split, splits;
   int tiles_m, tiles_n;
+  int sb_m, sb_n, n_sb_n, n_sb;  // super-blocks of sb_m x sb_n tiles (at most one XCD's worth, 32)
 };
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+// Epilogue shared by the GEMM kernels.  A lane holds, for each (tn, tm, g), output columns
+// n..n+3 of row m, with m = row0 + tm*32 + l32 and n = col0 + tn*32 + g*8 + kg*4.
+template <int TM, int TN>
+__device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)[TN][TM], int row0, int col0,
+                                              int l32, int kg, int split) {
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    const int m = row0 + tm * 32 + l32;
+    if (m >= p.M) continue;
+    if (p.splits > 1) {
+      float* dst = p.ws + ((int64_t)split * p.M + m) * p.Npad;
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = col0 + tn * 32 + g * 8 + kg * 4;
+          f32x4 v = {acc[tn][tm][g * 4 + 0], acc[tn][tm][g * 4 + 1], acc[tn][tm][g * 4 + 2],
+                     acc[tn][tm][g * 4 + 3]};
+          *reinterpret_cast<f32x4*>(dst + n) = v;
+        }
+    } else if (p.epilogue == EPI_SWIGLU) {
+#pragma unroll
+      for (int tn = 0; tn < TN; tn += 2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int j = (col0 + tn * 32) / 2 + g * 8 + kg * 4;
+          if (j < p.N_store) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              o[e] = (bf16)(silu_f(acc[tn][tm][g * 4 + e]) * acc[tn + 1][tm][g * 4 + e]);
+            *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + j) = o;
+          }
+        }
+    } else {
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n = col0 + tn * 32 + g * 8 + kg * 4;
+          if (n < p.N_store) {
+            float v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][g * 4 + e];
+            if (p.epilogue == EPI_RESIDUAL) {
+              bf16x4 r = *reinterpret_cast<const bf16x4*>(p.residual + (int64_t)m * p.ldr + n);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
+            }
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+            *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + n) = o;
+          }
+        }
+    }
+  }
+}
+
+// Workgroup -> (tile_m, tile_n, split).  Workgroups are dealt round-robin to the 8 XCDs, each
+// with its own L2, so the workgroups an XCD runs at once are given one compact sb_m x sb_n block
+// of tiles: they then share sb_m activation panels and sb_n weight panels in that L2.  Super-blocks
+// are numbered split-major, so with split-K an XCD also keeps to one K range.
+__device__ __forceinline__ bool gemm_tile_of_block(const GemmParams& p, int& tile_m, int& tile_n, int& split) {
+  const int xcd = blockIdx.x & 7;
+  const int local = blockIdx.x >> 3;
+  const int sb_size = p.sb_m * p.sb_n;
+  const int sb_global = (local / sb_size) * 8 + xcd;
+  if (sb_global >= p.n_sb * p.splits) return false;
+  split = sb_global / p.n_sb;
+  const int sb = sb_global % p.n_sb;
+  const int within = local % sb_size;
+  tile_m = (sb / p.n_sb_n) * p.sb_m + within % p.sb_m;
+  tile_n = (sb % p.n_sb_n) * p.sb_n + within / p.sb_m;
+  return tile_m < p.tiles_m && tile_n < p.tiles_n;
+}
+
+// 256 x 256 output tile fed by direct global->LDS loads (no staging registers).
+//   BK      k extent of one pipeline stage (64: 128-byte rows, 32: 64-byte rows)
+//   NS      stages resident in LDS; a stage's loads are issued NS-1 stages before they are used
+//   TM, TN  32x32 MFMA tiles per wave along m / n; waves = (8/TM) x (8/TN)
+// One global_load_lds instruction moves 64 lanes x 16 bytes into 1 KiB of LDS in lane order, so the
+// XOR swizzle is applied on the global side: the lane that fills chunk position c' of row r fetches
+// chunk c' ^ ((r / RW) % CPR) of that row (RW = rows per 256 bytes, CPR = 16-byte chunks per row).
+// With that swizzle the 16 lanes the LDS serves per cycle (16 consecutive rows of one logical
+// chunk) fall into 16 different 16-byte slots of the 64 banks: fragment reads are conflict free.
+template <int BK, int NS, int TM, int TN>
+__global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(const GemmParams p) {
+  constexpr int BM = 256, BN = 256;
+  constexpr int WAVES_N = 8 / TN, WAVES = (8 / TM) * WAVES_N;
+  constexpr int CPR = BK / 8;            // 16-byte chunks per row
+  constexpr int RW = 256 / (BK * 2);     // rows per 256-byte bank window
+  constexpr int RPI = 64 / CPR;          // rows per DMA instruction
+  constexpr int IPO = (256 / RPI) / WAVES;  // DMA instructions per wave per operand per stage
+  constexpr int KK = BK / 16;            // MFMA k-steps per stage
+  constexpr int AHEAD = NS - 1;
+  constexpr int STAGE = (BM + BN) * BK;  // elements per stage: A rows then W rows
+  constexpr int SPT = 64 / BK;           // stages per 64-wide k-tile
+  static_assert(TN % 2 == 0 && KK % 2 == 0, "gate/up pairing and fragment set parity");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);  // [NS][BM + BN][BK]
+
+  int tile_m, tile_n, split;
+  if (!gemm_tile_of_block(p, tile_m, tile_n, split)) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave / WAVES_N) * (TM * 32);
+  const int wn0 = (wave % WAVES_N) * (TN * 32);
+  const int l32 = lane & 31;
+  const int kg = lane >> 5;
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
+  const int kt_begin = split * p.k_tiles_per_split * SPT;
+  int kt_end = kt_begin + p.k_tiles_per_split * SPT;
+  if (kt_end > p.k_tiles_total * SPT) kt_end = p.k_tiles_total * SPT;
+  const int n_stages = kt_end - kt_begin;
+
+  // DMA assignment: wave w moves row blocks w*IPO .. w*IPO+IPO-1 (RPI rows each) of both operands
+  // Addresses are a wave-uniform 64-bit base (tile origin + k) plus a 32-bit per-lane offset.
+  const int r_in = lane / CPR;
+  unsigned a_goff[IPO], w_goff[IPO];
+#pragma unroll
+  for (int j = 0; j < IPO; ++j) {
+    const int row = (wave * IPO + j) * RPI + r_in;
+    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
+    int m = row;
+    if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
+    a_goff[j] = (unsigned)(m * (int)p.lda + c_sw * 8);
+    w_goff[j] = (unsigned)(row * (int)p.Kpad + c_sw * 8);
+  }
+  const bf16* a_base = p.A + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
+  const bf16* w_base = p.W + (int64_t)n0 * p.Kpad + (int64_t)kt_begin * BK;
+  auto dma_stage = [&](int t) {  // t relative to kt_begin; clamped so the tail re-fetches the last stage
+    const int tc = t < n_stages ? t : n_stages - 1;
+    const bf16* ab = a_base + (int64_t)tc * BK;
+    const bf16* wb = w_base + (int64_t)tc * BK;
+    bf16* la = smem + (t % NS) * STAGE + wave * IPO * RPI * BK;
+    bf16* lw = la + BM * BK;
+#pragma unroll
+    for (int j = 0; j < IPO; ++j) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ab + a_goff[j]),
+                                       (__attribute__((address_space(3))) void*)(la + j * RPI * BK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wb + w_goff[j]),
+                                       (__attribute__((address_space(3))) void*)(lw + j * RPI * BK), 16, 0, 0);
+    }
+  };
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[tn][tm][i] = 0.0f;
+
+  // fragment reads: per-lane row offsets are loop invariant, only the stage base moves
+  int w_off[TN], a_off[TM], w_sw[TN], a_sw[TM];
+#pragma unroll
+  for (int tn = 0; tn < TN; ++tn) {
+    const int r = wn0 + tn * 32 + l32;
+    w_off[tn] = (BM + r) * BK;
+    w_sw[tn] = (r / RW) % CPR;
+  }
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    const int r = wm0 + tm * 32 + l32;
+    a_off[tm] = r * BK;
+    a_sw[tm] = (r / RW) % CPR;
+  }
+  bf16x8 wf[2][TN], af[2][TM];
+  auto read_frags = [&](int t, int kk, int set) {
+    const bf16* base = smem + (t % NS) * STAGE;
+    const int chunk = kk * 2 + kg;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) wf[set][tn] = ld_bf16x8(base + w_off[tn] + ((chunk ^ w_sw[tn]) << 3));
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) af[set][tm] = ld_bf16x8(base + a_off[tm] + ((chunk ^ a_sw[tm]) << 3));
+  };
+  auto mfma_all = [&](int set) {
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[set][tn], af[set][tm], acc[tn][tm]);
+  };
+  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_DMA = 2 * IPO;
+  // A plain s_barrier is used, not __syncthreads(): its release fence would wait for ALL
+  // outstanding loads and defeat the prefetch distance.  vmcnt(PENDING) = this wave's loads of the
+  // next stage have landed; lgkmcnt(0) = its LDS reads of the buffer refilled next are complete.
+  constexpr int PENDING = (AHEAD - 1) * N_DMA;
+
+  if (n_stages > 0) {
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t) dma_stage(t);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+    read_frags(0, 0, 0);
+  }
+  for (int t = 0; t < n_stages; ++t) {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk == 0) dma_stage(t + AHEAD);  // into the buffer stage t-1 used: every wave has left it
+      if (kk == KK - 1) {
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+        read_frags(t + 1, 0, 0);
+      } else {
+        read_frags(t, kk + 1, (kk + 1) & 1);
+      }
+      mfma_all(kk & 1);
+#pragma unroll
+      for (int i = 0; i < N_MFMA; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (kk == 0 && i < N_DMA) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+      }
+    }
+  }
+  gemm_epilogue<TM, TN>(p, acc, m0 + wm0, n0 + wn0, l32, kg, split);
+}
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p) {
@@ -53,10 +276,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p) {
   const int l32 = lane & 31;
   const int kg = lane >> 5;
 
-  const int tile = blockIdx.x;
-  const int tile_n = tile % p.tiles_n;
-  const int tile_m = tile / p.tiles_n;
-  const int split = blockIdx.y;
+  int tile_m, tile_n, split;
+  if (!gemm_tile_of_block(p, tile_m, tile_n, split)) return;
   const int m0 = tile_m * BM;
   const int n0 = tile_n * BN;
   const int kt_begin = split * p.k_tiles_per_split;
@@ -89,12 +310,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p) {
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
       const int r = ld_row + 32 * j;
-      st_bf16x8(a + r * BK + ((ld_chunk ^ (r & 7)) << 3), a_reg[j]);
+      st_bf16x8(a + r * BK + ((ld_chunk ^ ((r >> 1) & 7)) << 3), a_reg[j]);
     }
 #pragma unroll
     for (int j = 0; j < W_LOADS; ++j) {
       const int r = ld_row + 32 * j;
-      st_bf16x8(w + r * BK + ((ld_chunk ^ (r & 7)) << 3), w_reg[j]);
+      st_bf16x8(w + r * BK + ((ld_chunk ^ ((r >> 1) & 7)) << 3), w_reg[j]);
     }
   };
 
@@ -106,94 +327,85 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[tn][tm][i] = 0.0f;
 
+  // MFMA fragments, double buffered in registers: the LDS reads of k-step kk+1 are issued
+  // while the MFMAs of k-step kk run.
+  bf16x8 wf[2][TN], af[2][TM];
+  auto read_frags = [&](int buf, int kk, int set) {
+    const bf16* a = sA + buf * BM * BK;
+    const bf16* w = sW + buf * BN * BK;
+    const int chunk = kk * 2 + kg;
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      const int r = wn0 + tn * 32 + l32;
+      wf[set][tn] = ld_bf16x8(w + r * BK + ((chunk ^ ((r >> 1) & 7)) << 3));
+    }
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+      const int r = wm0 + tm * 32 + l32;
+      af[set][tm] = ld_bf16x8(a + r * BK + ((chunk ^ ((r >> 1) & 7)) << 3));
+    }
+  };
+  auto mfma_all = [&](int set) {
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[set][tn], af[set][tm], acc[tn][tm]);
+  };
+  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_STAGE = A_LOADS + W_LOADS;
+  // Issue-order hints: spread `n_other` instructions of class `mask` evenly between the MFMAs.
+  // (0x008 MFMA, 0x020 VMEM read, 0x100 LDS read, 0x200 LDS write)
+
   if (kt_begin < kt_end) {
     load_global(kt_begin);
     store_lds(0);
   }
   __syncthreads();
+  read_frags(0, 0, 0);
 
   for (int kt = kt_begin; kt < kt_end; ++kt) {
     const int buf = (kt - kt_begin) & 1;
-    const bool more = kt + 1 < kt_end;
-    if (more) load_global(kt + 1);
-    const bf16* a = sA + buf * BM * BK;
-    const bf16* w = sW + buf * BN * BK;
+    // branch-free body: the last iteration stages its own tile again (never read)
+    const int kt_next = kt + 1 < kt_end ? kt + 1 : kt;
+    // k-step 0: global loads of the next tile go out, fragments of k-step 1 come in
+    load_global(kt_next);
+    read_frags(buf, 1, 1);
+    mfma_all(0);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int chunk = kk * 2 + kg;
-      bf16x8 wf[TN], af[TM];
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) {
-        const int r = wn0 + tn * 32 + l32;
-        wf[tn] = ld_bf16x8(w + r * BK + ((chunk ^ (r & 7)) << 3));
-      }
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm) {
-        const int r = wm0 + tm * 32 + l32;
-        af[tm] = ld_bf16x8(a + r * BK + ((chunk ^ (r & 7)) << 3));
-      }
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[tn], af[tm], acc[tn][tm]);
+    for (int i = 0; i < N_MFMA; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i < N_STAGE) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
-    if (more) store_lds(buf ^ 1);
+    // k-step 1
+    read_frags(buf, 2, 0);
+    mfma_all(1);
+#pragma unroll
+    for (int i = 0; i < N_MFMA; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    // k-step 2: the staged tile is written to the other LDS buffer
+    read_frags(buf, 3, 1);
+    store_lds(buf ^ 1);
+    mfma_all(0);
+#pragma unroll
+    for (int i = 0; i < N_MFMA; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i < N_STAGE) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+    }
     __syncthreads();
+    // k-step 3: fragments of the next tile's k-step 0 come in from the other buffer
+    read_frags(buf ^ 1, 0, 0);
+    mfma_all(1);
+#pragma unroll
+    for (int i = 0; i < N_MFMA; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
   }
 
-  // ---- epilogue: lane holds, for each (tn, tm, g), columns n..n+3 of row m -------------------
-#pragma unroll
-  for (int tm = 0; tm < TM; ++tm) {
-    const int m = m0 + wm0 + tm * 32 + l32;
-    if (m >= p.M) continue;
-    if (p.splits > 1) {
-      float* dst = p.ws + ((int64_t)split * p.M + m) * p.Npad;
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wn0 + tn * 32 + g * 8 + kg * 4;
-          f32x4 v = {acc[tn][tm][g * 4 + 0], acc[tn][tm][g * 4 + 1], acc[tn][tm][g * 4 + 2],
-                     acc[tn][tm][g * 4 + 3]};
-          *reinterpret_cast<f32x4*>(dst + n) = v;
-        }
-    } else if (p.epilogue == EPI_SWIGLU) {
-#pragma unroll
-      for (int tn = 0; tn < TN; tn += 2)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int j = (n0 + wn0 + tn * 32) / 2 + g * 8 + kg * 4;
-          if (j < p.N_store) {
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              o[e] = (bf16)(silu_f(acc[tn][tm][g * 4 + e]) * acc[tn + 1][tm][g * 4 + e]);
-            *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + j) = o;
-          }
-        }
-    } else {
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = n0 + wn0 + tn * 32 + g * 8 + kg * 4;
-          if (n < p.N_store) {
-            float v[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][g * 4 + e];
-            if (p.epilogue == EPI_RESIDUAL) {
-              bf16x4 r = *reinterpret_cast<const bf16x4*>(p.residual + (int64_t)m * p.ldr + n);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
-            }
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-            *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + n) = o;
-          }
-        }
-    }
-  }
+  gemm_epilogue<TM, TN>(p, acc, m0 + wm0, n0 + wn0, l32, kg, split);
 }
 
 // Sum the split-K partials and apply the epilogue.  One thread per 4 output columns.
@@ -231,12 +443,16 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
 struct TileInfo {
   int bm, bn, lds_bytes, wg_per_cu;
 };
-static const TileInfo kTiles[5] = {
+static const TileInfo kTiles[9] = {
     {0, 0, 0, 0},
     {256, 256, 2 * (256 + 256) * 128, 1},
     {128, 128, 2 * (128 + 128) * 128, 2},
     {64, 128, 2 * (64 + 128) * 128, 3},
     {32, 256, 2 * (32 + 256) * 128, 2},
+    {256, 256, 4 * 512 * 64, 1},   // 5: direct-to-LDS, BK 32 x 4 stages, 8 waves
+    {256, 256, 2 * 512 * 128, 1},  // 6: direct-to-LDS, BK 64 x 2 stages, 8 waves
+    {256, 256, 2 * 512 * 128, 1},  // 7: direct-to-LDS, BK 64 x 2 stages, 4 waves
+    {256, 256, 3 * 512 * 64, 1},   // 8: direct-to-LDS, BK 32 x 3 stages, 8 waves
 };
 
 hipError_t gemm_setup() {
@@ -252,13 +468,25 @@ hipError_t gemm_setup() {
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<32, 256, 1, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[4].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 4, 4, 2>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[5].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 2>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[6].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[7].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 3, 4, 2>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[8].lds_bytes);
   return e;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   int t = a.force_tile;
-  if (t < 1 || t > 4) t = a.M <= 32 ? 4 : a.M <= 64 ? 3 : a.M <= 128 ? 2 : 1;
+  if (t < 1 || t > 8) t = a.M <= 32 ? 4 : a.M <= 64 ? 3 : a.M <= 128 ? 2 : 6;
   const TileInfo& ti = kTiles[t];
   GemmParams p;
   p.A = (const bf16*)a.A;
@@ -277,29 +505,73 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.k_tiles_total = (int)(a.Kpad / 64);
   p.tiles_m = (a.M + ti.bm - 1) / ti.bm;
   p.tiles_n = (int)(a.Npad / ti.bn);
-  const int tiles = p.tiles_m * p.tiles_n;
-  int splits = a.force_splits;
-  if (splits <= 0) {
-    splits = 1;
-    if (a.M <= 512) {
-      const int target = 256 * ti.wg_per_cu;
-      splits = target / tiles;
-      if (splits > p.k_tiles_total / 4) splits = p.k_tiles_total / 4;
-      if (splits < 1) splits = 1;
+  // ---- plan: split-K factor and super-block size ---------------------------------------------
+  // The model: an XCD (32 CUs) works through the tiles dealt to it, wg_per_cu * 32 at a time, and a
+  // tile costs its k-tiles; split-K adds the fp32 partial round trip.  Small problems (decode) want
+  // every XCD equally loaded; large ones want 32-tile super-blocks for L2 reuse.
+  int max_splits = 1;
+  if (a.force_splits > 0) max_splits = a.force_splits;
+  else if (a.M <= 512) max_splits = p.k_tiles_total / 4 < 16 ? (p.k_tiles_total / 4 > 0 ? p.k_tiles_total / 4 : 1) : 16;
+  if (max_splits > p.k_tiles_total) max_splits = p.k_tiles_total;
+  double best_cost = 1e300;
+  int best_splits = 1, best_sb = 1;
+  for (int sp = a.force_splits > 0 ? max_splits : 1; sp <= max_splits; ++sp) {
+    if (sp > 1 && (int64_t)sp * a.M * a.Npad > a.workspace_elems) break;
+    const int per = (p.k_tiles_total + sp - 1) / sp;
+    const int real_sp = (p.k_tiles_total + per - 1) / per;
+    if (real_sp != sp && a.force_splits <= 0) continue;  // same schedule as a smaller factor
+    for (int sb_size = 32; sb_size >= 1; sb_size >>= 1) {
+      int sb_m = p.tiles_m >= 4 ? 4 : p.tiles_m >= 2 ? 2 : 1;
+      if (sb_m > sb_size) sb_m = sb_size;
+      const int sb_n = sb_size / sb_m;
+      const int n_sb_n = (p.tiles_n + sb_n - 1) / sb_n;
+      const int n_sb_m = (p.tiles_m + sb_m - 1) / sb_m;
+      const int n_sb = n_sb_m * n_sb_n;
+      int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      for (int g = 0; g < n_sb * real_sp; ++g) {
+        const int sb = g % n_sb;
+        const int rows = (sb / n_sb_n + 1) * sb_m <= p.tiles_m ? sb_m : p.tiles_m - (sb / n_sb_n) * sb_m;
+        const int cols = (sb % n_sb_n + 1) * sb_n <= p.tiles_n ? sb_n : p.tiles_n - (sb % n_sb_n) * sb_n;
+        load[g & 7] += (int64_t)rows * cols;
+      }
+      int64_t mx = 0;
+      for (int x = 0; x < 8; ++x) mx = load[x] > mx ? load[x] : mx;
+      const int slots = 32 * ti.wg_per_cu;
+      const double rounds = (double)((mx + slots - 1) / slots);
+      double cost = rounds * per;
+      // fp32 partials: 8 bytes per element and split at ~4 TB/s, in units of one k-tile round (~1.8 us)
+      if (real_sp > 1) cost += 1.1e-6 * real_sp * a.M * (double)a.Npad + 2.0;
+      cost *= 1.0 + 0.02 * (5 - __builtin_ctz(sb_size));  // prefer larger super-blocks on ties
+      if (cost < best_cost) {
+        best_cost = cost;
+        best_splits = real_sp;
+        best_sb = sb_size;
+      }
     }
   }
-  if (splits > p.k_tiles_total) splits = p.k_tiles_total;
-  while (splits > 1 && (int64_t)splits * a.M * a.Npad > a.workspace_elems) --splits;
+  int splits = best_splits;
   p.k_tiles_per_split = (p.k_tiles_total + splits - 1) / splits;
-  splits = (p.k_tiles_total + p.k_tiles_per_split - 1) / p.k_tiles_per_split;
   p.splits = splits;
-
-  dim3 grid(tiles, splits), block(256);
+  p.sb_m = p.tiles_m >= 4 ? 4 : p.tiles_m >= 2 ? 2 : 1;
+  if (p.sb_m > best_sb) p.sb_m = best_sb;
+  p.sb_n = best_sb / p.sb_m;
+  p.n_sb_n = (p.tiles_n + p.sb_n - 1) / p.sb_n;
+  p.n_sb = ((p.tiles_m + p.sb_m - 1) / p.sb_m) * p.n_sb_n;
+  static const bool print_plan = getenv("TDP_GEMM_PLAN") != nullptr;
+  if (print_plan)
+    fprintf(stderr, "gemm plan: M=%d N=%lld K=%lld tile=%d tiles=%dx%d splits=%d (k-tiles %d each) super-block %dx%d\n",
+            a.M, (long long)a.Npad, (long long)a.Kpad, t, p.tiles_m, p.tiles_n, splits, p.k_tiles_per_split, p.sb_m,
+            p.sb_n);
+  dim3 grid(((p.n_sb * splits + 7) / 8) * 8 * p.sb_m * p.sb_n), block(256);
   switch (t) {
     case 1: gemm_kernel<256, 256, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
     case 2: gemm_kernel<128, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
     case 3: gemm_kernel<64, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
-    default: gemm_kernel<32, 256, 1, 4><<<grid, block, ti.lds_bytes, s>>>(p); break;
+    case 4: gemm_kernel<32, 256, 1, 4><<<grid, block, ti.lds_bytes, s>>>(p); break;
+    case 5: gemm_dma_kernel<32, 4, 4, 2><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 6: gemm_dma_kernel<64, 2, 4, 2><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 7: gemm_dma_kernel<64, 2, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    default: gemm_dma_kernel<32, 3, 4, 2><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
