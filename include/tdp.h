@@ -156,6 +156,14 @@ TDP_API int tdp_stage_decode(tdp_stage* st, const void* hidden_in, const int32_t
                      const int32_t* block_tables, int32_t batch, void* hidden_out, void* stream);
 
 /*
+ * Restrict the following prefill/decode calls to layers [first, first + count) of the stage, as
+ * if the stage were that sub-slice (a finer pipeline split, or a layer-by-layer check against a
+ * reference).  The hand-over format at both ends stays bf16.  count = 0 restores the whole stage.
+ * Errors: TDP_EINVAL when the range does not lie inside [0, n_layers).
+ */
+TDP_API int tdp_stage_set_layer_range(tdp_stage* st, int32_t first, int32_t count);
+
+/*
  * Diagnostic: one projection GEMM through the library's kernels, out = A * W with W given as
  * a row-major [K, N] bf16 device matrix (repacked internally on every call: not a fast path).
  * A dev bf16 [M][K]; out dev bf16 [M][N].  K multiple of 64, N multiple of 4.

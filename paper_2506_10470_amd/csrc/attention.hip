@@ -58,35 +58,42 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16* __restrict_
   const int last_page = (n_total - 1) / 16;
   // token of this lane's row in score tile t: (r16/4)*8 + t*4 + r16%4
   const int krow0 = (r16 >> 2) * 8 + (r16 & 3);
+  // The chunk's page ids (at most kDecodeChunk/16 + 1 <= 64) are fetched once, lane i holding the
+  // i-th; the loop then reads them with v_readlane, so no table load sits between two blocks.
+  // Entries past the last valid page are clamped to it: they are never dereferenced otherwise.
+  const int page_base = t_begin >> 4;
+  const int my_pages = bt[min(page_base + lane, last_page)];
 
-  for (int tb = t_begin; tb < t_end; tb += 32) {
-    const int p0 = tb >> 4;
-    const int p1 = min(p0 + 1, last_page);  // never dereference a table entry past the last page
-    const int64_t page0 = bt[p0], page1 = bt[p1];
-
+  // One 32-token block = the K fragments of two score tiles and the V^T fragments of all channel
+  // tiles: 16 KiB per wave (head_dim 128), fetched one block ahead of the MFMAs that consume it.
+  struct Block {
     bf16x8 kf[2][KS];
+    bf16x8 vf[DT];
+  };
+  auto load_block = [&](int tb, Block& blk) {
+    const int pi = (tb >> 4) - page_base;
+    const int64_t page0 = __builtin_amdgcn_readlane(my_pages, pi);
+    const int64_t page1 = __builtin_amdgcn_readlane(my_pages, pi + 1);
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int tok = krow0 + t * 4;
       const int64_t page = tok < 16 ? page0 : page1;
       const bf16* kp = kpool + ((page * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) kf[t][kk] = ld_bf16x8(kp + kk * 32);
+      for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8(kp + kk * 32);
     }
-    bf16x8 vf[DT];
-    {
-      const int64_t page = kg < 2 ? page0 : page1;
-      const bf16* vp = vpool + ((page * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
+    const int64_t page = kg < 2 ? page0 : page1;
+    const bf16* vp = vpool + ((page * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
 #pragma unroll
-      for (int d = 0; d < DT; ++d) vf[d] = ld_bf16x8(vp + d * 16 * 16);
-    }
-
+    for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8(vp + d * 16 * 16);
+  };
+  auto compute_block = [&](int tb, Block& blk) {
     f32x4 s[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) s[t] = mfma16(kf[t][kk], qf[kk], s[t]);
+      for (int kk = 0; kk < KS; ++kk) s[t] = mfma16(blk.kf[t][kk], qf[kk], s[t]);
     }
     // lane holds tokens tb + kg*8 + t*4 + i of column q = r16
     const int tok_base = tb + kg * 8;
@@ -120,12 +127,26 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16* __restrict_
       for (int d = 0; d < DT; ++d)
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          if (tok_base + j >= n_total) vf[d][j] = (bf16)0.0f;
+          if (tok_base + j >= n_total) blk.vf[d][j] = (bf16)0.0f;
     }
 #pragma unroll
     for (int d = 0; d < DT; ++d) {
       o[d] *= alpha;
-      o[d] = mfma16(vf[d], pb, o[d]);
+      o[d] = mfma16(blk.vf[d], pb, o[d]);
+    }
+  };
+
+  // two blocks per trip, ping-pong between two register sets; a prefetch past the end of the
+  // chunk re-reads the chunk's last block (valid memory, never used)
+  const int tb_last = t_begin + ((t_end - t_begin - 1) & ~31);
+  Block b0, b1;
+  load_block(t_begin, b0);
+  for (int tb = t_begin; tb < t_end; tb += 64) {
+    load_block(min(tb + 32, tb_last), b1);
+    compute_block(tb, b0);
+    if (tb + 32 < t_end) {
+      load_block(min(tb + 64, tb_last), b0);
+      compute_block(tb + 32, b1);
     }
   }
   lsum += __shfl_xor(lsum, 16, 64);

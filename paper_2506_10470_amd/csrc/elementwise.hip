@@ -14,22 +14,40 @@
 namespace tdp {
 
 // ------------------------------------------------------------------ RMSNorm
-// y = x * g / sqrt(mean(x^2) + eps); one workgroup per row, fp32 statistics.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16* __restrict__ x, int64_t ldx,
+// y = x * g / sqrt(mean(x^2) + eps); one workgroup per row, fp32 statistics.  x is the residual
+// stream: bf16 as handed over by the previous stage, fp32 between the layers of this stage.
+template <bool F32_IN>
+__device__ __forceinline__ void load8(const void* row, int c, float (&f)[8]) {
+  if (F32_IN) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>((const float*)row + c * 8);
+    const f32x4 b = *reinterpret_cast<const f32x4*>((const float*)row + c * 8 + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[i] = a[i];
+      f[i + 4] = b[i];
+    }
+  } else {
+    const bf16x8 v = ld_bf16x8((const bf16*)row + c * 8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)v[i];
+  }
+}
+
+template <bool F32_IN>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x, int64_t ldx,
                                                       const float* __restrict__ gain, float eps, int d,
                                                       bf16* __restrict__ y, int64_t ldy) {
   const int row = blockIdx.x;
-  const bf16* xr = x + (int64_t)row * ldx;
+  const void* xr = F32_IN ? (const void*)((const float*)x + (int64_t)row * ldx)
+                          : (const void*)((const bf16*)x + (int64_t)row * ldx);
   bf16* yr = y + (int64_t)row * ldy;
   const int chunks = d / 8;
   float ss = 0.f;
   for (int c = threadIdx.x; c < chunks; c += 256) {
-    bf16x8 v = ld_bf16x8(xr + c * 8);
+    float f[8];
+    load8<F32_IN>(xr, c, f);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float f = (float)v[i];
-      ss += f * f;
-    }
+    for (int i = 0; i < 8; ++i) ss += f[i] * f[i];
   }
   __shared__ float red[4];
   ss = wave_sum(ss);
@@ -38,23 +56,27 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const bf16* __restrict__ x
   const float tot = red[0] + red[1] + red[2] + red[3];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
   for (int c = threadIdx.x; c < chunks; c += 256) {
-    bf16x8 v = ld_bf16x8(xr + c * 8);
+    float f[8];
+    load8<F32_IN>(xr, c, f);
     const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c * 8);
     const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + c * 8 + 4);
     bf16x8 o;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      o[i] = (bf16)((float)v[i] * inv * g0[i]);
-      o[i + 4] = (bf16)((float)v[i + 4] * inv * g1[i]);
+      o[i] = (bf16)(f[i] * inv * g0[i]);
+      o[i + 4] = (bf16)(f[i + 4] * inv * g1[i]);
     }
     st_bf16x8(yr + c * 8, o);
   }
 }
 
-hipError_t launch_rmsnorm(const void* x, int64_t ldx, const float* gain, float eps, int M, int d,
+hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float* gain, float eps, int M, int d,
                           void* y, int64_t ldy, hipStream_t s) {
   if (M <= 0) return hipSuccess;
-  rmsnorm_kernel<<<M, 256, 0, s>>>((const bf16*)x, ldx, gain, eps, d, (bf16*)y, ldy);
+  if (x_is_f32)
+    rmsnorm_kernel<true><<<M, 256, 0, s>>>(x, ldx, gain, eps, d, (bf16*)y, ldy);
+  else
+    rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, ldx, gain, eps, d, (bf16*)y, ldy);
   return hipGetLastError();
 }
 

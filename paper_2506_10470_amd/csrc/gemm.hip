@@ -24,16 +24,39 @@ struct GemmParams {
   const bf16* A;
   const bf16* W;
   bf16* out;
-  const bf16* residual;
+  const void* residual;  // bf16, or fp32 when res_f32
   float* ws;
   int64_t lda, Kpad, Npad, ldo, ldr;
-  int M, N_store, epilogue;
+  int M, N_store, epilogue, out_f32, res_f32;
   int k_tiles_total, k_tiles_per_split, splits;
   int tiles_m, tiles_n;
   int sb_m, sb_n, n_sb_n, n_sb;  // super-blocks of sb_m x sb_n tiles (at most one XCD's worth, 32)
 };
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+// Residual add and store of four consecutive output columns (plain / residual epilogues).
+__device__ __forceinline__ void store_row4(const GemmParams& p, int m, int n, float (&v)[4]) {
+  if (p.epilogue == EPI_RESIDUAL) {
+    if (p.res_f32) {
+      const f32x4 r = *reinterpret_cast<const f32x4*>((const float*)p.residual + (int64_t)m * p.ldr + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] += r[e];
+    } else {
+      const bf16x4 r = *reinterpret_cast<const bf16x4*>((const bf16*)p.residual + (int64_t)m * p.ldr + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
+    }
+  }
+  if (p.out_f32) {
+    *reinterpret_cast<f32x4*>((float*)p.out + (int64_t)m * p.ldo + n) = f32x4{v[0], v[1], v[2], v[3]};
+  } else {
+    bf16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+    *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + n) = o;
+  }
+}
 
 // Epilogue shared by the GEMM kernels.  A lane holds, for each (tn, tm, g), output columns
 // n..n+3 of row m, with m = row0 + tm*32 + l32 and n = col0 + tn*32 + g*8 + kg*4.
@@ -79,15 +102,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)
             float v[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][g * 4 + e];
-            if (p.epilogue == EPI_RESIDUAL) {
-              bf16x4 r = *reinterpret_cast<const bf16x4*>(p.residual + (int64_t)m * p.ldr + n);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
-            }
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-            *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + n) = o;
+            store_row4(p, m, n, v);
           }
         }
     }
@@ -421,23 +436,18 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
       s += *reinterpret_cast<const f32x4*>(p.ws + ((int64_t)z * p.M + m) * p.Npad + n);
     return s;
   };
-  bf16x4 o;
   if (p.epilogue == EPI_SWIGLU) {
     const int ng = (j / 32) * 64 + (j % 32);
     f32x4 g = sum_at(ng), u = sum_at(ng + 32);
+    bf16x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = (bf16)(silu_f(g[e]) * u[e]);
+    *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + j) = o;
   } else {
-    f32x4 v = sum_at(j);
-    if (p.epilogue == EPI_RESIDUAL) {
-      bf16x4 r = *reinterpret_cast<const bf16x4*>(p.residual + (int64_t)m * p.ldr + j);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] += (float)r[e];
-    }
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+    const f32x4 t = sum_at(j);
+    float v[4] = {t[0], t[1], t[2], t[3]};
+    store_row4(p, m, j, v);
   }
-  *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + j) = o;
 }
 
 struct TileInfo {
@@ -492,7 +502,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.A = (const bf16*)a.A;
   p.W = (const bf16*)a.W;
   p.out = (bf16*)a.out;
-  p.residual = (const bf16*)a.residual;
+  p.residual = a.residual;
+  p.out_f32 = a.epilogue == EPI_RESIDUAL ? a.out_f32 : 0;
+  p.res_f32 = a.residual_f32;
   p.ws = a.workspace;
   p.lda = a.lda;
   p.Kpad = a.Kpad;

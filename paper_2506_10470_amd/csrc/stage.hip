@@ -43,8 +43,8 @@ struct tdp_stage {
   float *g_attn = nullptr, *g_mlp = nullptr;
   uint16_t *kpool = nullptr, *vpool = nullptr;
   int64_t pool_elems = 0;  // per layer, per pool
-  uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *h = nullptr, *u = nullptr, *xa = nullptr,
-           *xb = nullptr;
+  uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *u = nullptr;  // bf16 activations
+  float *h = nullptr, *xa = nullptr, *xb = nullptr;  // residual stream, fp32 between layers
   float* ws = nullptr;
   int64_t ws_elems = 0;
   float *part_o = nullptr, *part_ml = nullptr;
@@ -52,6 +52,7 @@ struct tdp_stage {
   float2* rope_table = nullptr;
   int max_pos = 0;
   int maxM = 0;
+  int layer_first = 0, layer_count = 0;  // count 0 = all layers
   bool timing = false;
   std::vector<hipEvent_t> ev_start, ev_stop;
   std::vector<int> ev_class;
@@ -132,14 +133,20 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
   const tdp_stage_config& c = st->cfg;
   const int64_t d = c.d_model;
   st->ev_used = 0;
-  const uint16_t* x = (const uint16_t*)hidden_in;
-  int64_t ldx = d;
-  for (int l = 0; l < c.n_layers; ++l) {
+  // The residual stream enters and leaves the stage as bf16 (the pipeline's hand-over format) and
+  // is kept in fp32 in between: two bf16 roundings per layer would otherwise pile up over a
+  // 20-layer stage to more than the 2e-2 parity bound.
+  const void* x = hidden_in;
+  int x_f32 = 0;
+  const int l_begin = st->layer_count > 0 ? st->layer_first : 0;
+  const int l_end = st->layer_count > 0 ? st->layer_first + st->layer_count : c.n_layers;
+  for (int l = l_begin; l < l_end; ++l) {
     const KvLayout kv = kv_layout(st, l);
-    uint16_t* x_next = (l == c.n_layers - 1) ? (uint16_t*)hidden_out : ((l & 1) ? st->xb : st->xa);
+    const bool last = l == l_end - 1;
+    void* x_next = last ? hidden_out : (void*)((l & 1) ? st->xb : st->xa);
     {  // a1: pre-attention RMSNorm
       Timer t(st, s, T_NORM);
-      HIP_TRY(launch_rmsnorm(x, ldx, st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
+      HIP_TRY(launch_rmsnorm(x, x_f32, d, st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
     }
     GemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -151,7 +158,7 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
       g.A = st->y; g.lda = d;
       g.W = st->wqkv + (int64_t)l * st->Nqkv_pad * d; g.Kpad = d; g.Npad = st->Nqkv_pad;
       g.N_store = (int)st->Nqkv_pad; g.out = st->qkv; g.ldo = st->Nqkv_pad;
-      g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE;
+      g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE; g.out_f32 = 0; g.residual_f32 = 0;
       HIP_TRY(launch_gemm(g, s));
     }
     {  // a3: rotary embedding + KV append
@@ -169,36 +176,36 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
         HIP_TRY(launch_attn_prefill(st->qkv, st->Nqkv_pad, M, n_seqs, c.n_q_heads, kv, cu_seqlens, block_tables,
                                     c.max_pages_per_seq, st->attn, st->dq, s));
     }
-    {  // a5: output projection + residual
+    {  // a5: output projection + residual -> h (fp32)
       Timer t(st, s, T_O);
       g.A = st->attn; g.lda = st->dq;
       g.W = st->wo + (int64_t)l * st->d_pad * st->dq; g.Kpad = st->dq; g.Npad = st->d_pad;
-      g.N_store = (int)d; g.out = st->h; g.ldo = d;
-      g.residual = x; g.ldr = ldx; g.epilogue = EPI_RESIDUAL;
+      g.N_store = (int)d; g.out = st->h; g.ldo = d; g.out_f32 = 1;
+      g.residual = x; g.ldr = d; g.residual_f32 = x_f32; g.epilogue = EPI_RESIDUAL;
       HIP_TRY(launch_gemm(g, s));
     }
     {  // a6: pre-MLP RMSNorm
       Timer t(st, s, T_NORM);
-      HIP_TRY(launch_rmsnorm(st->h, d, st->g_mlp + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
+      HIP_TRY(launch_rmsnorm(st->h, 1, d, st->g_mlp + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
     }
     {  // a7: gate/up projection + SwiGLU
       Timer t(st, s, T_GU);
       g.A = st->y; g.lda = d;
       g.W = st->wgu + (int64_t)l * st->Ngu_pad * d; g.Kpad = d; g.Npad = st->Ngu_pad;
-      g.N_store = (int)st->Fpad; g.out = st->u; g.ldo = st->Fpad;
-      g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_SWIGLU;
+      g.N_store = (int)st->Fpad; g.out = st->u; g.ldo = st->Fpad; g.out_f32 = 0;
+      g.residual = nullptr; g.ldr = 0; g.residual_f32 = 0; g.epilogue = EPI_SWIGLU;
       HIP_TRY(launch_gemm(g, s));
     }
-    {  // a8: down projection + residual
+    {  // a8: down projection + residual -> next layer's stream (fp32), or the stage output (bf16)
       Timer t(st, s, T_DOWN);
       g.A = st->u; g.lda = st->Fpad;
       g.W = st->wd + (int64_t)l * st->d_pad * st->Fpad; g.Kpad = st->Fpad; g.Npad = st->d_pad;
-      g.N_store = (int)d; g.out = x_next; g.ldo = d;
-      g.residual = st->h; g.ldr = d; g.epilogue = EPI_RESIDUAL;
+      g.N_store = (int)d; g.out = x_next; g.ldo = d; g.out_f32 = last ? 0 : 1;
+      g.residual = st->h; g.ldr = d; g.residual_f32 = 1; g.epilogue = EPI_RESIDUAL;
       HIP_TRY(launch_gemm(g, s));
     }
     x = x_next;
-    ldx = d;
+    x_f32 = 1;
   }
   return TDP_OK;
 }
@@ -451,6 +458,19 @@ int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out,
   if (wt) (void)hipFree(wt);
   if (ws) (void)hipFree(ws);
   if (e != hipSuccess) return fail_hip(e, "tdp_gemm_bf16");
+  return TDP_OK;
+}
+
+int tdp_stage_set_layer_range(tdp_stage* st, int32_t first, int32_t count) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (count == 0) {
+    st->layer_first = st->layer_count = 0;
+    return TDP_OK;
+  }
+  if (first < 0 || count < 0 || first + count > st->cfg.n_layers)
+    return fail(TDP_EINVAL, "layer range outside the stage");
+  st->layer_first = first;
+  st->layer_count = count;
   return TDP_OK;
 }
 

@@ -21,11 +21,13 @@ struct GemmArgs {
   int64_t Npad;       // multiple of 256
   int M;
   int N_store;        // columns of `out` that exist (SWIGLU: Npad/2 is stored up to N_store)
-  void* out;          // bf16 [M][ldo]
+  void* out;          // [M][ldo], bf16 unless out_f32
   int64_t ldo;
-  const void* residual;  // bf16 [M][ldr] or null
+  const void* residual;  // [M][ldr] or null, bf16 unless residual_f32
   int64_t ldr;
   int epilogue;
+  int out_f32;        // EPI_RESIDUAL only: the residual stream is kept in fp32 inside a stage
+  int residual_f32;
   float* workspace;       // fp32 split-K partials
   int64_t workspace_elems;
   int force_tile;         // 0 = choose; else 1..4 selects a tile shape (tests / tuning)
@@ -41,7 +43,7 @@ hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in /*K*/,
 hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float* dst, hipStream_t s);
 
 // ---- RMSNorm ---------------------------------------------------------------------------------
-hipError_t launch_rmsnorm(const void* x, int64_t ldx, const float* gain, float eps, int M, int d,
+hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float* gain, float eps, int M, int d,
                           void* y, int64_t ldy, hipStream_t s);
 
 // ---- RoPE + KV append ------------------------------------------------------------------------

@@ -9,7 +9,7 @@ import os
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtdp.so")
+LIB_PATH = os.environ.get("TDP_LIB", os.path.join(_HERE, "libtdp.so"))   # TDP_LIB: alternative build
 
 OK, EINVAL, ENOMEM, EHIP = 0, -1, -2, -3
 WQ, WK, WV, WO, WG, WU, WD, G_ATTN, G_MLP = range(9)
@@ -55,6 +55,7 @@ _SIGS = {
     "tdp_stage_kv_export": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
     "tdp_stage_prefill": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "tdp_stage_decode": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "tdp_stage_set_layer_range": (C.c_int, [_vp, _i32, _i32]),
     "tdp_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "tdp_stage_timing_enable": (C.c_int, [_vp, _i32]),
     "tdp_stage_timing_read": (C.c_int, [_vp, C.POINTER(C.c_float)]),
@@ -136,6 +137,10 @@ def tdp_stage_prefill(st, hidden_in, cu_seqlens, block_tables, n_seqs, total_tok
 def tdp_stage_decode(st, hidden_in, ctx_lens, block_tables, batch, hidden_out, stream=None) -> None:
     _check(lib.tdp_stage_decode(st, _ptr(hidden_in), _ptr(ctx_lens), _ptr(block_tables), batch,
                                 _ptr(hidden_out), _stream(stream)))
+
+
+def tdp_stage_set_layer_range(st, first: int, count: int) -> None:
+    _check(lib.tdp_stage_set_layer_range(st, first, count))
 
 
 def tdp_gemm_bf16(A, W, residual, out, M, N, K, epilogue=0, tile=0, splits=0, stream=None) -> None:

@@ -50,3 +50,31 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     denom = np.max(np.abs(ref), axis=-1)
     denom = np.where(denom == 0, 1.0, denom)
     return float(np.max(np.max(np.abs(got - ref), axis=-1) / denom))
+
+
+def bf16_round(a: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even to bf16, returned as float64."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+def layer_forward_bf16_operands(x, k_cache, v_cache, w: O.LayerWeights, sh: O.Shape):
+    """The oracle's layer, composed from the oracle's own primitives, with every tensor that a
+    bf16-operand implementation must hold in bf16 rounded to bf16 (norm outputs, q, k, v before and
+    after rotation, attention output, SwiGLU output) and ALL arithmetic left in fp64.  Its distance
+    to the unrounded oracle is the error floor of any such implementation on this input: it
+    measures the precision, not a kernel."""
+    rb = bf16_round
+    x = np.asarray(x, np.float64)
+    L, p0 = x.shape[0], k_cache.shape[0]
+    pos = np.arange(p0, p0 + L)
+    y = rb(O.rmsnorm(x, w.g_attn, sh.rms_eps))
+    q = rb(O.rope(rb(y @ w.wq).reshape(L, sh.n_q_heads, sh.head_dim), pos, sh.rope_base))
+    k = rb(O.rope(rb(y @ w.wk).reshape(L, sh.n_kv_heads, sh.head_dim), pos, sh.rope_base))
+    v = rb(y @ w.wv).reshape(L, sh.n_kv_heads, sh.head_dim)
+    k_all = np.concatenate([np.asarray(k_cache, np.float64), k], axis=0)
+    v_all = np.concatenate([np.asarray(v_cache, np.float64), v], axis=0)
+    a = rb(O.attention(q, k_all, v_all, p0, sh))
+    h = x + a @ w.wo
+    y2 = rb(O.rmsnorm(h, w.g_mlp, sh.rms_eps))
+    u = rb(O.silu(y2 @ w.wg) * (y2 @ w.wu))
+    return h + u @ w.wd, k_all, v_all
