@@ -118,6 +118,22 @@ def kernel_rooflines(shape, M, kv_read_bytes, attn_flops, times_ms, phase):
     return res
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 TCC counters (committed under profiles/, see the
+    summary there for the commands); None when no measurement exists for this workload."""
+    path = os.path.join(ROOT, "profiles", "traffic_decode_70b_quarter_b512.json")
+    try:
+        t = json.load(open(path))
+    except OSError:
+        return {}
+    if t.get("workload") != workload:
+        return {}
+    per = t["per_launch"]
+    tot = lambda *ks: sum(per[k]["fetch_bytes"] + per[k]["write_bytes"] for k in ks if k in per)
+    return {"attention": tot("attn_decode_kernel", "attn_decode_merge_kernel"), "gemm_qkv": tot("gemm_qkv"),
+            "gemm_o": tot("gemm_o"), "gemm_gate_up": tot("gemm_gate_up"), "gemm_down": tot("gemm_down")}
+
+
 def cpu_baseline(shape, dec_ctx, cu, budget_layers=4, n_requests=64):
     """The fp64 oracle, as it stands, on a bounded sample of the decode workload: `n_requests`
     requests spread evenly over the batch sorted by context length (shortest and longest included)
@@ -176,6 +192,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size kernel that rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (pipeline stages would each run "
@@ -208,6 +227,13 @@ def main():
     def decode_fn(b=B):
         tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, b, out, stream)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)            # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- headline: decode at the full batch
     ms = time_calls(decode_fn, args.warmup, args.steps)
     work = A.decode_step_work(*sargs, dec_ctx)
@@ -215,6 +241,10 @@ def main():
                                                                           work["bytes"] / ms / 1e6))
     ct = class_times(tdp, st, decode_fn, 5)
     kern = kernel_rooflines(shape, B, work["kv_read_bytes"], work["attn_flops"], ct, "decode")
+    workload_name = "%s stage, decode phase, batch %d" % (args.workload, B)
+    for name, tr in measured_traffic(workload_name).items():
+        if name in kern and not args.layers:
+            kern[name]["traffic"] = tr
     dominant = max(kern, key=lambda k: ct[k])
     roof = dict(kern[dominant])
     roof["kernel"] = dominant
@@ -227,7 +257,7 @@ def main():
         "value": round(B / ms * 1e3, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s stage, decode phase, batch %d" % (args.workload, B),
+        "config": {"workload": workload_name,
                    "n_layers": shape.n_layers, "d_model": shape.d_model, "n_q_heads": shape.n_q_heads,
                    "n_kv_heads": shape.n_kv_heads, "head_dim": shape.head_dim, "d_ff": shape.d_ff,
                    "batch": B, "mean_ctx": round(float(dec_ctx.mean()), 1), "max_ctx": int(dec_ctx.max()),
