@@ -129,22 +129,27 @@ __device__ __forceinline__ bool gemm_tile_of_block(const GemmParams& p, int& til
 
 // 256 x 256 output tile fed by direct global->LDS loads (no staging registers).
 //   BK      k extent of one pipeline stage (64: 128-byte rows, 32: 64-byte rows)
-//   NS      stages resident in LDS; a stage's loads are issued NS-1 stages before they are used
+//   NS      stages resident in LDS; a stage's loads are issued NS-1 barriers before they are used
 //   TM, TN  32x32 MFMA tiles per wave along m / n; waves = (8/TM) x (8/TN)
+//   LOADERS waves that issue the global->LDS loads: all of them, or only the upper half (one per
+//           SIMD), so that while a loader wave is held up at load issue its SIMD-mate, which never
+//           touches the memory pipe, keeps the MFMA unit fed
 // One global_load_lds instruction moves 64 lanes x 16 bytes into 1 KiB of LDS in lane order, so the
 // XOR swizzle is applied on the global side: the lane that fills chunk position c' of row r fetches
 // chunk c' ^ ((r / RW) % CPR) of that row (RW = rows per 256 bytes, CPR = 16-byte chunks per row).
 // With that swizzle the 16 lanes the LDS serves per cycle (16 consecutive rows of one logical
 // chunk) fall into 16 different 16-byte slots of the 64 banks: fragment reads are conflict free.
-template <int BK, int NS, int TM, int TN>
+template <int BK, int NS, int TM, int TN, int LOADERS>
 __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(const GemmParams p) {
   constexpr int BM = 256, BN = 256;
   constexpr int WAVES_N = 8 / TN, WAVES = (8 / TM) * WAVES_N;
   constexpr int CPR = BK / 8;            // 16-byte chunks per row
   constexpr int RW = 256 / (BK * 2);     // rows per 256-byte bank window
   constexpr int RPI = 64 / CPR;          // rows per DMA instruction
-  constexpr int IPO = (256 / RPI) / WAVES;  // DMA instructions per wave per operand per stage
   constexpr int KK = BK / 16;            // MFMA k-steps per stage
+  constexpr int IPO = (256 / RPI) / LOADERS;  // DMA instructions per loader wave per operand per stage
+  static_assert(LOADERS == WAVES || LOADERS * 2 == WAVES, "all waves load, or the upper half");
+  static_assert(KK >= 2 && IPO % 2 == 0, "a stage's loads are issued in two halves");
   constexpr int AHEAD = NS - 1;
   constexpr int STAGE = (BM + BN) * BK;  // elements per stage: A rows then W rows
   constexpr int SPT = 64 / BK;           // stages per 64-wide k-tile
@@ -168,13 +173,15 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
   if (kt_end > p.k_tiles_total * SPT) kt_end = p.k_tiles_total * SPT;
   const int n_stages = kt_end - kt_begin;
 
-  // DMA assignment: wave w moves row blocks w*IPO .. w*IPO+IPO-1 (RPI rows each) of both operands
-  // Addresses are a wave-uniform 64-bit base (tile origin + k) plus a 32-bit per-lane offset.
+  // DMA assignment: loader wave lw moves row blocks lw*IPO .. lw*IPO+IPO-1 (RPI rows each) of both
+  // operands.  Addresses are a wave-uniform 64-bit base (tile origin + k) plus a 32-bit per-lane offset.
+  const bool is_loader = wave >= WAVES - LOADERS;
+  const int lw_id = is_loader ? wave - (WAVES - LOADERS) : 0;
   const int r_in = lane / CPR;
   unsigned a_goff[IPO], w_goff[IPO];
 #pragma unroll
   for (int j = 0; j < IPO; ++j) {
-    const int row = (wave * IPO + j) * RPI + r_in;
+    const int row = (lw_id * IPO + j) * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
     int m = row;
     if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
@@ -183,14 +190,15 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
   }
   const bf16* a_base = p.A + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
   const bf16* w_base = p.W + (int64_t)n0 * p.Kpad + (int64_t)kt_begin * BK;
-  auto dma_stage = [&](int t) {  // t relative to kt_begin; clamped so the tail re-fetches the last stage
+  // t relative to kt_begin, clamped so the tail re-fetches the last stage; half 0 / 1 of the loads
+  auto dma_stage = [&](int t, int half) {
     const int tc = t < n_stages ? t : n_stages - 1;
     const bf16* ab = a_base + (int64_t)tc * BK;
     const bf16* wb = w_base + (int64_t)tc * BK;
-    bf16* la = smem + (t % NS) * STAGE + wave * IPO * RPI * BK;
+    bf16* la = smem + (t % NS) * STAGE + lw_id * IPO * RPI * BK;
     bf16* lw = la + BM * BK;
 #pragma unroll
-    for (int j = 0; j < IPO; ++j) {
+    for (int j = half * (IPO / 2); j < (half + 1) * (IPO / 2); ++j) {
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ab + a_goff[j]),
                                        (__attribute__((address_space(3))) void*)(la + j * RPI * BK), 16, 0, 0);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wb + w_goff[j]),
@@ -235,25 +243,41 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[set][tn], af[set][tm], acc[tn][tm]);
   };
-  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_DMA = 2 * IPO;
+  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_DMA = 2 * IPO;  // N_DMA per loader wave per stage
   // A plain s_barrier is used, not __syncthreads(): its release fence would wait for ALL
   // outstanding loads and defeat the prefetch distance.  vmcnt(PENDING) = this wave's loads of the
   // next stage have landed; lgkmcnt(0) = its LDS reads of the buffer refilled next are complete.
-  constexpr int PENDING = (AHEAD - 1) * N_DMA;
+  constexpr int PENDING = (NS - 2) * N_DMA;
 
+  // Pipeline.  The one barrier of stage t sits before its last k-step: by then every wave has
+  // issued (and waited for) its LDS reads of stage t, so right after the barrier buffer t % NS is
+  // refilled with stage t + NS - the loads get a whole stage of MFMA time, barrier to barrier - and
+  // the first fragments of stage t + 1 are read under the last k-step's MFMAs.
   if (n_stages > 0) {
+    if (is_loader) {
 #pragma unroll
-    for (int t = 0; t < AHEAD; ++t) dma_stage(t);
+      for (int t = 0; t < NS - 1; ++t) {
+        dma_stage(t, 0);
+        dma_stage(t, 1);
+      }
+    }
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
     read_frags(0, 0, 0);
+    if (is_loader) {
+      dma_stage(NS - 1, 0);
+      dma_stage(NS - 1, 1);
+    }
   }
   for (int t = 0; t < n_stages; ++t) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      if (kk == 0) dma_stage(t + AHEAD);  // into the buffer stage t-1 used: every wave has left it
       if (kk == KK - 1) {
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
         read_frags(t + 1, 0, 0);
+        if (is_loader) {
+          dma_stage(t + NS, 0);
+          dma_stage(t + NS, 1);
+        }
       } else {
         read_frags(t, kk + 1, (kk + 1) & 1);
       }
@@ -262,7 +286,7 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
       for (int i = 0; i < N_MFMA; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (kk == 0 && i < N_DMA) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+        if (kk == KK - 1) __builtin_amdgcn_sched_group_barrier(0x010, (N_DMA + N_MFMA - 1) / N_MFMA, 0);
       }
     }
   }
@@ -460,9 +484,9 @@ static const TileInfo kTiles[9] = {
     {64, 128, 2 * (64 + 128) * 128, 3},
     {32, 256, 2 * (32 + 256) * 128, 2},
     {256, 256, 4 * 512 * 64, 1},   // 5: direct-to-LDS, BK 32 x 4 stages, 8 waves
-    {256, 256, 2 * 512 * 128, 1},  // 6: direct-to-LDS, BK 64 x 2 stages, 8 waves
+    {256, 256, 2 * 512 * 128, 1},  // 6: direct-to-LDS, BK 64 x 2 stages, 8 waves, 4 of them load
     {256, 256, 2 * 512 * 128, 1},  // 7: direct-to-LDS, BK 64 x 2 stages, 4 waves
-    {256, 256, 3 * 512 * 64, 1},   // 8: direct-to-LDS, BK 32 x 3 stages, 8 waves
+    {256, 256, 2 * 512 * 128, 1},  // 8: direct-to-LDS, BK 64 x 2 stages, 8 waves, every wave loads
 };
 
 hipError_t gemm_setup() {
@@ -479,16 +503,16 @@ hipError_t gemm_setup() {
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<32, 256, 1, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[4].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 4, 4, 2>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 4, 4, 2, 8>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[5].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 2>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 2, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[6].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 4>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 4, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[7].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 3, 4, 2>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 2, 8>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[8].lds_bytes);
   return e;
 }
@@ -580,10 +604,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     case 2: gemm_kernel<128, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
     case 3: gemm_kernel<64, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
     case 4: gemm_kernel<32, 256, 1, 4><<<grid, block, ti.lds_bytes, s>>>(p); break;
-    case 5: gemm_dma_kernel<32, 4, 4, 2><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 6: gemm_dma_kernel<64, 2, 4, 2><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 7: gemm_dma_kernel<64, 2, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    default: gemm_dma_kernel<32, 3, 4, 2><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 5: gemm_dma_kernel<32, 4, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 6: gemm_dma_kernel<64, 2, 4, 2, 4><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 7: gemm_dma_kernel<64, 2, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    default: gemm_dma_kernel<64, 2, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
