@@ -520,7 +520,7 @@ hipError_t gemm_setup() {
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   int t = a.force_tile;
-  if (t < 1 || t > 8) t = a.M <= 32 ? 4 : a.M <= 64 ? 3 : a.M <= 128 ? 2 : 6;
+  if (t < 1 || t > 8) t = a.M <= 32 ? 4 : a.M <= 64 ? 3 : a.M <= 128 ? 2 : 8;
   const TileInfo& ti = kTiles[t];
   GemmParams p;
   p.A = (const bf16*)a.A;
