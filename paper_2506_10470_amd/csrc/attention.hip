@@ -19,29 +19,71 @@ namespace tdp {
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf: exp2 gives exactly 0, no inf-inf
 
 // =====================================================================================
-// Decode: one wave per (chunk of the KV range, kv head, request).
+// Decode.  Work item = (request, span of span_len tokens of its context); one workgroup
+// of four waves per (item, kv head).  The four waves split the span's 32-token blocks evenly and
+// merge their partial softmax states through LDS; a request whose context fits one span is
+// finished there (no partials in HBM), longer ones leave one partial per span for the merge
+// kernel.  The item list is compact (built once per decode step by attn_plan_kernel), so the grid
+// holds no workgroup that finds nothing to do except at its very end.
 // =====================================================================================
+
+// items[i] = (request, span index); n_items[0] = count.  One workgroup, any batch size.
+__global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restrict__ ctx_lens, int batch, int span_len,
+                                                        int2* __restrict__ items, int32_t* __restrict__ n_items) {
+  __shared__ int part[256];
+  const int tid = threadIdx.x;
+  const int per = (batch + 255) / 256;
+  const int b0 = tid * per, b1 = min(b0 + per, batch);
+  int cnt = 0;
+  for (int b = b0; b < b1; ++b) cnt += (ctx_lens[b] + span_len) / span_len;
+  part[tid] = cnt;
+  __syncthreads();
+  if (tid == 0) {
+    int acc = 0;
+    for (int i = 0; i < 256; ++i) {
+      const int c = part[i];
+      part[i] = acc;
+      acc += c;
+    }
+    n_items[0] = acc;
+  }
+  __syncthreads();
+  int pos = part[tid];
+  for (int b = b0; b < b1; ++b) {
+    const int n = (ctx_lens[b] + span_len) / span_len;
+    for (int k = 0; k < n; ++k) items[pos++] = make_int2(b, k);
+  }
+}
+
 template <int DH>
-__global__ __launch_bounds__(64) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
-                                                         int n_q_heads, KvLayout kv,
-                                                         const int32_t* __restrict__ ctx_lens,
-                                                         const int32_t* __restrict__ block_tables,
-                                                         int max_pages_per_seq, float* __restrict__ part_o,
-                                                         float* __restrict__ part_ml, int max_chunks,
-                                                         float scale_log2) {
+__global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
+                                                          int n_q_heads, KvLayout kv,
+                                                          const int32_t* __restrict__ ctx_lens,
+                                                          const int32_t* __restrict__ block_tables,
+                                                          int max_pages_per_seq, const int2* __restrict__ items,
+                                                          const int32_t* __restrict__ n_items,
+                                                          float* __restrict__ part_o, float* __restrict__ part_ml,
+                                                          int max_spans, int span_len, bf16* __restrict__ out,
+                                                          int64_t ldo, float scale_log2) {
   constexpr int KS = DH / 32;   // k-steps of the score MFMA
   constexpr int DT = DH / 16;   // 16-channel tiles of the output
-  const int chunk = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int n_total = ctx_lens[b] + 1;  // the new token's K/V were appended before this kernel
-  const int t_begin = chunk * kDecodeChunk;
-  if (t_begin >= n_total) return;
-  const int t_end = min(t_begin + kDecodeChunk, n_total);
   const int Hkv = kv.n_kv_heads;
+  const int item = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
+  if (item >= n_items[0]) return;
+  const int2 it = items[item];
+  const int b = it.x, span = it.y;
+  const int n_total = ctx_lens[b] + 1;  // the new token's K/V were appended before this kernel
+  const int s_begin = span * span_len;
+  const int s_end = min(s_begin + span_len, n_total);
   const int G = n_q_heads / Hkv;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const bf16* kpool = (const bf16*)kv.k_pool;
   const bf16* vpool = (const bf16*)kv.v_pool;
+  // this wave's share of the span, in whole 32-token blocks
+  const int n_blocks = (s_end - s_begin + 31) >> 5;
+  const int t_begin = s_begin + 32 * ((wave * n_blocks) >> 2);
+  const int t_end = min(s_begin + 32 * (((wave + 1) * n_blocks) >> 2), s_end);
 
   bf16x8 qf[KS];
   {
@@ -54,131 +96,154 @@ __global__ __launch_bounds__(64) void attn_decode_kernel(const bf16* __restrict_
   for (int d = 0; d < DT; ++d) o[d] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m = kNegBig, lsum = 0.f;
 
-  const int32_t* bt = block_tables + (int64_t)b * max_pages_per_seq;
-  const int last_page = (n_total - 1) / 16;
-  // token of this lane's row in score tile t: (r16/4)*8 + t*4 + r16%4
-  const int krow0 = (r16 >> 2) * 8 + (r16 & 3);
-  // The chunk's page ids (at most kDecodeChunk/16 + 1 <= 64) are fetched once, lane i holding the
-  // i-th; the loop then reads them with v_readlane, so no table load sits between two blocks.
-  // Entries past the last valid page are clamped to it: they are never dereferenced otherwise.
-  const int page_base = t_begin >> 4;
-  const int my_pages = bt[min(page_base + lane, last_page)];
+  if (t_begin < t_end) {
+    const int32_t* bt = block_tables + (int64_t)b * max_pages_per_seq;
+    const int last_page = (n_total - 1) / 16;
+    // token of this lane's row in score tile t: (r16/4)*8 + t*4 + r16%4
+    const int krow0 = (r16 >> 2) * 8 + (r16 & 3);
+    // The wave's page ids (at most span_len/64 + 1 <= 17) are fetched once, lane i holding the
+    // i-th; the loop reads them with v_readlane, so no table load sits between two blocks.
+    // Entries past the last valid page are clamped to it: they are never dereferenced otherwise.
+    const int page_base = t_begin >> 4;
+    const int my_pages = bt[min(page_base + lane, last_page)];
 
-  // One 32-token block = the K fragments of two score tiles and the V^T fragments of all channel
-  // tiles: 16 KiB per wave (head_dim 128), fetched one block ahead of the MFMAs that consume it.
-  struct Block {
-    bf16x8 kf[2][KS];
-    bf16x8 vf[DT];
-  };
-  auto load_block = [&](int tb, Block& blk) {
-    const int pi = (tb >> 4) - page_base;
-    const int64_t page0 = __builtin_amdgcn_readlane(my_pages, pi);
-    const int64_t page1 = __builtin_amdgcn_readlane(my_pages, pi + 1);
+    // One 32-token block = the K fragments of two score tiles and the V^T fragments of all channel
+    // tiles: 16 KiB per wave (head_dim 128), fetched one block ahead of the MFMAs that consume it.
+    struct Block {
+      bf16x8 kf[2][KS];
+      bf16x8 vf[DT];
+    };
+    auto load_block = [&](int tb, Block& blk) {
+      const int pi = (tb >> 4) - page_base;
+      const int64_t page0 = __builtin_amdgcn_readlane(my_pages, pi);
+      const int64_t page1 = __builtin_amdgcn_readlane(my_pages, pi + 1);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int tok = krow0 + t * 4;
-      const int64_t page = tok < 16 ? page0 : page1;
-      const bf16* kp = kpool + ((page * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
+      for (int t = 0; t < 2; ++t) {
+        const int tok = krow0 + t * 4;
+        const int64_t page = tok < 16 ? page0 : page1;
+        const bf16* kp = kpool + ((page * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8(kp + kk * 32);
-    }
-    const int64_t page = kg < 2 ? page0 : page1;
-    const bf16* vp = vpool + ((page * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
-#pragma unroll
-    for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8(vp + d * 16 * 16);
-  };
-  auto compute_block = [&](int tb, Block& blk) {
-    f32x4 s[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) s[t] = mfma16(blk.kf[t][kk], qf[kk], s[t]);
-    }
-    // lane holds tokens tb + kg*8 + t*4 + i of column q = r16
-    const int tok_base = tb + kg * 8;
-    float mx = kNegBig;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float v = (tok_base + t * 4 + i < n_total) ? s[t][i] * scale_log2 : kNegBig;
-        s[t][i] = v;
-        mx = fmaxf(mx, v);
+        for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8(kp + kk * 32);
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = exp2f(m - m_new);
-    bf16x8 pb;
-    float psum = 0.f;
+      const int64_t page = kg < 2 ? page0 : page1;
+      const bf16* vp = vpool + ((page * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+      for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8(vp + d * 16 * 16);
+    };
+    auto compute_block = [&](int tb, Block& blk) {
+      f32x4 s[2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float pv = exp2f(s[t][i] - m_new);
-        psum += pv;
-        pb[t * 4 + i] = (bf16)pv;
+      for (int t = 0; t < 2; ++t) {
+        s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) s[t] = mfma16(blk.kf[t][kk], qf[kk], s[t]);
       }
-    lsum = lsum * alpha + psum;
-    m = m_new;
-    if (tb + 32 > n_total) {  // tail: slots past the context may hold anything, even NaN
+      // lane holds tokens tb + kg*8 + t*4 + i of column q = r16
+      const int tok_base = tb + kg * 8;
+      float mx = kNegBig;
 #pragma unroll
-      for (int d = 0; d < DT; ++d)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (tok_base + j >= n_total) blk.vf[d][j] = (bf16)0.0f;
-    }
+        for (int i = 0; i < 4; ++i) {
+          const float v = (tok_base + t * 4 + i < n_total) ? s[t][i] * scale_log2 : kNegBig;
+          s[t][i] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m, mx);
+      const float alpha = exp2f(m - m_new);
+      bf16x8 pb;
+      float psum = 0.f;
 #pragma unroll
-    for (int d = 0; d < DT; ++d) {
-      o[d] *= alpha;
-      o[d] = mfma16(blk.vf[d], pb, o[d]);
-    }
-  };
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float pv = exp2f(s[t][i] - m_new);
+          psum += pv;
+          pb[t * 4 + i] = (bf16)pv;
+        }
+      lsum = lsum * alpha + psum;
+      m = m_new;
+      if (tb + 32 > n_total) {  // tail: slots past the context may hold anything, even NaN
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (tok_base + j >= n_total) blk.vf[d][j] = (bf16)0.0f;
+      }
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        o[d] *= alpha;
+        o[d] = mfma16(blk.vf[d], pb, o[d]);
+      }
+    };
 
-  // two blocks per trip, ping-pong between two register sets; a prefetch past the end of the
-  // chunk re-reads the chunk's last block (valid memory, never used)
-  const int tb_last = t_begin + ((t_end - t_begin - 1) & ~31);
-  Block b0, b1;
-  load_block(t_begin, b0);
-  for (int tb = t_begin; tb < t_end; tb += 64) {
-    load_block(min(tb + 32, tb_last), b1);
-    compute_block(tb, b0);
-    if (tb + 32 < t_end) {
-      load_block(min(tb + 64, tb_last), b0);
-      compute_block(tb + 32, b1);
+    // two blocks per trip, ping-pong between two register sets; a prefetch past the end of the
+    // wave's range re-reads its last block (valid memory, never used)
+    const int tb_last = t_begin + ((t_end - t_begin - 1) & ~31);
+    Block b0, b1;
+    load_block(t_begin, b0);
+    for (int tb = t_begin; tb < t_end; tb += 64) {
+      load_block(min(tb + 32, tb_last), b1);
+      compute_block(tb, b0);
+      if (tb + 32 < t_end) {
+        load_block(min(tb + 64, tb_last), b0);
+        compute_block(tb + 32, b1);
+      }
     }
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
   }
-  lsum += __shfl_xor(lsum, 16, 64);
-  lsum += __shfl_xor(lsum, 32, 64);
 
-  if (r16 < G) {
-    const int h = kvh * G + r16;
-    const int64_t slot = ((int64_t)b * n_q_heads + h) * max_chunks + chunk;
-    float* po = part_o + slot * DH + kg * 4;
+  // ---- merge the four waves' states through LDS (fixed wave order: results do not depend on
+  // which physical pages held the tokens)
+  __shared__ float s_o[4][16][DH + 4];
+  __shared__ float s_m[4][16], s_l[4][16];
 #pragma unroll
-    for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(po + d * 16) = o[d];
-    if (kg == 0) {
-      part_ml[slot * 2 + 0] = m;
-      part_ml[slot * 2 + 1] = lsum;
+  for (int d = 0; d < DT; ++d) *reinterpret_cast<f32x4*>(&s_o[wave][r16][d * 16 + kg * 4]) = o[d];
+  if (kg == 0) {
+    s_m[wave][r16] = m;
+    s_l[wave][r16] = lsum;
+  }
+  __syncthreads();
+  const int n_spans = (n_total + span_len - 1) / span_len;
+  for (int e = threadIdx.x; e < G * DH; e += 256) {
+    const int q = e / DH, c = e % DH;
+    const float m0 = s_m[0][q], m1 = s_m[1][q], m2 = s_m[2][q], m3 = s_m[3][q];
+    const float mt = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+    const float w0 = exp2f(m0 - mt), w1 = exp2f(m1 - mt), w2 = exp2f(m2 - mt), w3 = exp2f(m3 - mt);
+    const float num = w0 * s_o[0][q][c] + w1 * s_o[1][q][c] + w2 * s_o[2][q][c] + w3 * s_o[3][q][c];
+    const float den = w0 * s_l[0][q] + w1 * s_l[1][q] + w2 * s_l[2][q] + w3 * s_l[3][q];
+    const int h = kvh * G + q;
+    if (n_spans == 1) {
+      out[(int64_t)b * ldo + (int64_t)h * DH + c] = (bf16)(num / den);
+    } else {
+      const int64_t slot = ((int64_t)b * n_q_heads + h) * max_spans + span;
+      part_o[slot * DH + c] = num;
+      if (c == 0) {
+        part_ml[slot * 2 + 0] = mt;
+        part_ml[slot * 2 + 1] = den;
+      }
     }
   }
 }
 
-// Merge the per-chunk partials: out = sum_c o_c 2^(m_c - m) / sum_c l_c 2^(m_c - m).
+// Requests longer than one span: out = sum_s o_s 2^(m_s - m) / sum_s l_s 2^(m_s - m).
 template <int DH>
 __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __restrict__ part_o,
                                                                const float* __restrict__ part_ml,
                                                                const int32_t* __restrict__ ctx_lens,
-                                                               int n_q_heads, int max_chunks,
+                                                               int n_q_heads, int max_spans, int span_len,
                                                                bf16* __restrict__ out, int64_t ldo) {
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
-  const int n_chunks = min((ctx_lens[b] + 1 + kDecodeChunk - 1) / kDecodeChunk, max_chunks);
-  const int64_t base = ((int64_t)b * n_q_heads + h) * max_chunks;
+  const int n_spans = min((ctx_lens[b] + span_len) / span_len, max_spans);
+  if (n_spans <= 1) return;  // finished by the attention kernel itself
+  const int64_t base = ((int64_t)b * n_q_heads + h) * max_spans;
   float m = kNegBig;
-  for (int k = 0; k < n_chunks; ++k) m = fmaxf(m, part_ml[(base + k) * 2]);
+  for (int k = 0; k < n_spans; ++k) m = fmaxf(m, part_ml[(base + k) * 2]);
   float num = 0.f, den = 0.f;
-  for (int k = 0; k < n_chunks; ++k) {
+  for (int k = 0; k < n_spans; ++k) {
     const float w = exp2f(part_ml[(base + k) * 2] - m);
     den += w * part_ml[(base + k) * 2 + 1];
     num += w * part_o[(base + k) * DH + c];
@@ -186,23 +251,42 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
   out[(int64_t)b * ldo + (int64_t)h * DH + c] = (bf16)(num / den);
 }
 
+// Span length: long spans (fewer partials; most requests finish inside one workgroup) unless the
+// batch is so small that parallelism has to come from splitting each context.  Measured on the
+// 70B shape: 1024 beats 256 from batch 16 up.
+int attn_decode_span(int batch, int n_kv_heads) { return batch * n_kv_heads >= 128 ? kDecodeSpanMax : kDecodeSpanMin; }
+
+hipError_t launch_attn_plan(const int32_t* ctx_lens, int batch, int span_len, int2* items, int32_t* n_items,
+                            hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  attn_plan_kernel<<<1, 256, 0, s>>>(ctx_lens, batch, span_len, items, n_items);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
                               const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq,
-                              float* part_o, float* part_ml, int max_chunks, void* out, int64_t ldo,
-                              hipStream_t s) {
+                              const int2* items, const int32_t* n_items, float* part_o, float* part_ml,
+                              int max_spans, int span_len, void* out, int64_t ldo, hipStream_t s) {
   if (batch <= 0) return hipSuccess;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
-  dim3 grid(max_chunks, kv.n_kv_heads, batch), mgrid(n_q_heads, batch);
+  // max_spans counts spans of the minimum length; longer spans need proportionally fewer slots
+  const int spans = (max_spans * kDecodeSpanMin + span_len - 1) / span_len;
+  const unsigned grid = (unsigned)batch * spans * kv.n_kv_heads;
+  dim3 mgrid(n_q_heads, batch);
   if (kv.head_dim == 128) {
-    attn_decode_kernel<128><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
-                                                max_pages_per_seq, part_o, part_ml, max_chunks, scale_log2);
-    attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_chunks,
-                                                        (bf16*)out, ldo);
+    attn_decode_kernel<128><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
+                                                 max_pages_per_seq, items, n_items, part_o, part_ml, max_spans,
+                                                 span_len, (bf16*)out, ldo, scale_log2);
+    if (spans > 1)
+      attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
+                                                          span_len, (bf16*)out, ldo);
   } else {
-    attn_decode_kernel<64><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
-                                               max_pages_per_seq, part_o, part_ml, max_chunks, scale_log2);
-    attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_chunks,
-                                                      (bf16*)out, ldo);
+    attn_decode_kernel<64><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
+                                                max_pages_per_seq, items, n_items, part_o, part_ml, max_spans,
+                                                span_len, (bf16*)out, ldo, scale_log2);
+    if (spans > 1)
+      attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
+                                                        span_len, (bf16*)out, ldo);
   }
   return hipGetLastError();
 }
