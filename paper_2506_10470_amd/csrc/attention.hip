@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict
                                                           const int32_t* __restrict__ n_items,
                                                           float* __restrict__ part_o, float* __restrict__ part_ml,
                                                           int max_spans, int span_len, bf16* __restrict__ out,
-                                                          int64_t ldo, float scale_log2) {
+                                                          OperandLayout out_lay, float scale_log2) {
   constexpr int KS = DH / 32;   // k-steps of the score MFMA
   constexpr int DT = DH / 16;   // 16-channel tiles of the output
   const int Hkv = kv.n_kv_heads;
@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict
     const float den = w0 * s_l[0][q] + w1 * s_l[1][q] + w2 * s_l[2][q] + w3 * s_l[3][q];
     const int h = kvh * G + q;
     if (n_spans == 1) {
-      out[(int64_t)b * ldo + (int64_t)h * DH + c] = (bf16)(num / den);
+      out[operand_offset(out_lay, b, h * DH + c)] = (bf16)(num / den);
     } else {
       const int64_t slot = ((int64_t)b * n_q_heads + h) * max_spans + span;
       part_o[slot * DH + c] = num;
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
                                                                const float* __restrict__ part_ml,
                                                                const int32_t* __restrict__ ctx_lens,
                                                                int n_q_heads, int max_spans, int span_len,
-                                                               bf16* __restrict__ out, int64_t ldo) {
+                                                               bf16* __restrict__ out, OperandLayout out_lay) {
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
   const int n_spans = min((ctx_lens[b] + span_len) / span_len, max_spans);
   if (n_spans <= 1) return;  // finished by the attention kernel itself
@@ -248,7 +248,7 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
     den += w * part_ml[(base + k) * 2 + 1];
     num += w * part_o[(base + k) * DH + c];
   }
-  out[(int64_t)b * ldo + (int64_t)h * DH + c] = (bf16)(num / den);
+  out[operand_offset(out_lay, b, h * DH + c)] = (bf16)(num / den);
 }
 
 // Span length: long spans (fewer partials; most requests finish inside one workgroup) unless the
@@ -266,7 +266,7 @@ hipError_t launch_attn_plan(const int32_t* ctx_lens, int batch, int span_len, in
 hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
                               const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq,
                               const int2* items, const int32_t* n_items, float* part_o, float* part_ml,
-                              int max_spans, int span_len, void* out, int64_t ldo, hipStream_t s) {
+                              int max_spans, int span_len, void* out, OperandLayout out_layout, hipStream_t s) {
   if (batch <= 0) return hipSuccess;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
   // max_spans counts spans of the minimum length; longer spans need proportionally fewer slots
@@ -276,17 +276,17 @@ hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_he
   if (kv.head_dim == 128) {
     attn_decode_kernel<128><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
                                                  max_pages_per_seq, items, n_items, part_o, part_ml, max_spans,
-                                                 span_len, (bf16*)out, ldo, scale_log2);
+                                                 span_len, (bf16*)out, out_layout, scale_log2);
     if (spans > 1)
       attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
-                                                          span_len, (bf16*)out, ldo);
+                                                          span_len, (bf16*)out, out_layout);
   } else {
     attn_decode_kernel<64><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
                                                 max_pages_per_seq, items, n_items, part_o, part_ml, max_spans,
-                                                span_len, (bf16*)out, ldo, scale_log2);
+                                                span_len, (bf16*)out, out_layout, scale_log2);
     if (spans > 1)
       attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
-                                                        span_len, (bf16*)out, ldo);
+                                                        span_len, (bf16*)out, out_layout);
   }
   return hipGetLastError();
 }
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(64) void attn_prefill_kernel(const bf16* __restrict
                                                           const int32_t* __restrict__ cu_seqlens, int n_seqs,
                                                           const int32_t* __restrict__ block_tables,
                                                           int max_pages_per_seq, bf16* __restrict__ out,
-                                                          int64_t ldo, float scale_log2) {
+                                                          OperandLayout out_lay, float scale_log2) {
   constexpr int KS = DH / 16;  // k-steps of the score MFMA
   constexpr int DT = DH / 32;  // 32-channel tiles of the output
   const int h = blockIdx.y;
@@ -398,7 +398,6 @@ __global__ __launch_bounds__(64) void attn_prefill_kernel(const bf16* __restrict
   lsum += __shfl_xor(lsum, 32, 64);
   if (qpos < L) {
     const float inv = 1.0f / lsum;
-    bf16* op = out + (int64_t)(tok0 + qpos) * ldo + (int64_t)h * DH + kg * 4;
 #pragma unroll
     for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -406,23 +405,23 @@ __global__ __launch_bounds__(64) void attn_prefill_kernel(const bf16* __restrict
         bf16x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[d][g * 4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(op + d * 32 + g * 8) = v;
+        *reinterpret_cast<bf16x4*>(out + operand_offset(out_lay, tok0 + qpos, h * DH + d * 32 + g * 8 + kg * 4)) = v;
       }
   }
 }
 
 hipError_t launch_attn_prefill(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
                                const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
-                               int max_pages_per_seq, void* out, int64_t ldo, hipStream_t s) {
+                               int max_pages_per_seq, void* out, OperandLayout out_layout, hipStream_t s) {
   if (total_tokens <= 0 || n_seqs <= 0) return hipSuccess;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
   dim3 grid((total_tokens + 31) / 32 + n_seqs, n_q_heads);
   if (kv.head_dim == 128)
     attn_prefill_kernel<128><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
-                                                 block_tables, max_pages_per_seq, (bf16*)out, ldo, scale_log2);
+                                                 block_tables, max_pages_per_seq, (bf16*)out, out_layout, scale_log2);
   else
     attn_prefill_kernel<64><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
-                                                block_tables, max_pages_per_seq, (bf16*)out, ldo, scale_log2);
+                                                block_tables, max_pages_per_seq, (bf16*)out, out_layout, scale_log2);
   return hipGetLastError();
 }
 

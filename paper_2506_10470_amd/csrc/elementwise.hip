@@ -36,11 +36,10 @@ __device__ __forceinline__ void load8(const void* row, int c, float (&f)[8]) {
 template <bool F32_IN>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x, int64_t ldx,
                                                       const float* __restrict__ gain, float eps, int d,
-                                                      bf16* __restrict__ y, int64_t ldy) {
+                                                      bf16* __restrict__ y, OperandLayout y_lay) {
   const int row = blockIdx.x;
   const void* xr = F32_IN ? (const void*)((const float*)x + (int64_t)row * ldx)
                           : (const void*)((const bf16*)x + (int64_t)row * ldx);
-  bf16* yr = y + (int64_t)row * ldy;
   const int chunks = d / 8;
   float ss = 0.f;
   for (int c = threadIdx.x; c < chunks; c += 256) {
@@ -66,17 +65,17 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
       o[i] = (bf16)(f[i] * inv * g0[i]);
       o[i + 4] = (bf16)(f[i + 4] * inv * g1[i]);
     }
-    st_bf16x8(yr + c * 8, o);
+    st_bf16x8(y + operand_offset(y_lay, row, c * 8), o);
   }
 }
 
 hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float* gain, float eps, int M, int d,
-                          void* y, int64_t ldy, hipStream_t s) {
+                          void* y, OperandLayout y_layout, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (x_is_f32)
-    rmsnorm_kernel<true><<<M, 256, 0, s>>>(x, ldx, gain, eps, d, (bf16*)y, ldy);
+    rmsnorm_kernel<true><<<M, 256, 0, s>>>(x, ldx, gain, eps, d, (bf16*)y, y_layout);
   else
-    rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, ldx, gain, eps, d, (bf16*)y, ldy);
+    rmsnorm_kernel<false><<<M, 256, 0, s>>>(x, ldx, gain, eps, d, (bf16*)y, y_layout);
   return hipGetLastError();
 }
 
@@ -201,7 +200,8 @@ hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const Kv
 }
 
 // ------------------------------------------------------------------ weight repack (one-time)
-// dst[row_of(n)][k] = bf16(src[k][n]) through a 32x32 LDS transpose.
+// dst(row_of(n), k) = bf16(src[k][n]) through a 32x32 LDS transpose; dst is pair-interleaved
+// (rows 2p, 2p+1 alternate in 32-column blocks) with dst_ld columns.
 __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ src, int src_is_f32,
                                                      int64_t K, int64_t N, bf16* __restrict__ dst,
                                                      int64_t dst_ld, int64_t row_off, int mode) {
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ sr
       int64_t row;
       if (mode == 0) row = row_off + n;
       else row = (n / 32) * 64 + (n % 32) + (mode == 2 ? 32 : 0);
-      dst[row * dst_ld + k] = (bf16)tile[tx][r];
+      dst[(row >> 1) * 2 * dst_ld + (k >> 5) * 64 + (row & 1) * 32 + (k & 31)] = (bf16)tile[tx][r];
     }
   }
 }

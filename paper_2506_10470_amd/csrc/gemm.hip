@@ -1,7 +1,8 @@
 // bf16 MFMA GEMM for the stage's four projections (paper Sec. 3.4: linear layers dominate the
 // execution time of a decode step, and only the batch size sets their cost).
 //
-//   out[M, N] = epilogue( A[M, K] * W^T ),   A bf16 [M][lda],  W bf16 [Npad][Kpad]  (K contiguous)
+//   out[M, N] = epilogue( A[M, K] * W^T ),   A bf16 M x K,  W bf16 Npad x Kpad  (both K-contiguous in
+//   32-column blocks; W and the stage's own activations are pair-interleaved, see OperandLayout)
 //
 // Both operands are K-contiguous, so an MFMA fragment is one 16-byte load.  The product is formed
 // transposed, D[n][m] = sum_k W[n][k] A[m][k], with the weights as the MFMA "A" operand: a lane
@@ -26,7 +27,8 @@ struct GemmParams {
   bf16* out;
   const void* residual;  // bf16, or fp32 when res_f32
   float* ws;
-  int64_t lda, Kpad, Npad, ldo, ldr;
+  OperandLayout a_lay, w_lay, u_lay;
+  int64_t Kpad, Npad, ldo, ldr;
   int M, N_store, epilogue, out_f32, res_f32;
   int k_tiles_total, k_tiles_per_split, splits;
   int tiles_m, tiles_n;
@@ -89,7 +91,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
               o[e] = (bf16)(silu_f(acc[tn][tm][g * 4 + e]) * acc[tn + 1][tm][g * 4 + e]);
-            *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + j) = o;
+            *reinterpret_cast<bf16x4*>(p.out + operand_offset(p.u_lay, m, j)) = o;
           }
         }
     } else {
@@ -182,19 +184,20 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
 #pragma unroll
   for (int j = 0; j < IPO; ++j) {
     const int row = (lw_id * IPO + j) * RPI + r_in;
-    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
+    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);  // 16-byte chunk of the stage's k range
     int m = row;
     if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
-    a_goff[j] = (unsigned)(m * (int)p.lda + c_sw * 8);
-    w_goff[j] = (unsigned)(row * (int)p.Kpad + c_sw * 8);
+    a_goff[j] = (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + (c_sw >> 2) * p.a_lay.kb + (c_sw & 3) * 8);
+    w_goff[j] = (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + (c_sw >> 2) * p.w_lay.kb + (c_sw & 3) * 8);
   }
-  const bf16* a_base = p.A + (int64_t)m0 * p.lda + (int64_t)kt_begin * BK;
-  const bf16* w_base = p.W + (int64_t)n0 * p.Kpad + (int64_t)kt_begin * BK;
+  constexpr int KB_PER_STAGE = BK / 32;
+  const bf16* a_base = p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * KB_PER_STAGE * p.a_lay.kb;
+  const bf16* w_base = p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * KB_PER_STAGE * p.w_lay.kb;
   // t relative to kt_begin, clamped so the tail re-fetches the last stage; half 0 / 1 of the loads
   auto dma_stage = [&](int t, int half) {
     const int tc = t < n_stages ? t : n_stages - 1;
-    const bf16* ab = a_base + (int64_t)tc * BK;
-    const bf16* wb = w_base + (int64_t)tc * BK;
+    const bf16* ab = a_base + (int64_t)tc * KB_PER_STAGE * p.a_lay.kb;
+    const bf16* wb = w_base + (int64_t)tc * KB_PER_STAGE * p.w_lay.kb;
     bf16* la = smem + (t % NS) * STAGE + lw_id * IPO * RPI * BK;
     bf16* lw = la + BM * BK;
 #pragma unroll
@@ -331,17 +334,19 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p) {
   for (int j = 0; j < A_LOADS; ++j) {
     int m = m0 + ld_row + 32 * j;
     if (m > p.M - 1) m = p.M - 1;  // rows past M are clamped: computed, never stored
-    a_ptr[j] = p.A + (int64_t)m * p.lda + ld_chunk * 8;
+    a_ptr[j] = p.A + (int64_t)(m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + (ld_chunk >> 2) * p.a_lay.kb +
+               (ld_chunk & 3) * 8;
   }
-  const bf16* w_ptr = p.W + (int64_t)(n0 + ld_row) * p.Kpad + ld_chunk * 8;
+  // weight rows 32 j apart keep their parity, so one base pointer and a pair stride serve all of them
+  const bf16* w_ptr = p.W + (int64_t)((n0 + ld_row) >> 1) * p.w_lay.pair + ((n0 + ld_row) & 1) * p.w_lay.par +
+                      (ld_chunk >> 2) * p.w_lay.kb + (ld_chunk & 3) * 8;
 
   bf16x8 a_reg[A_LOADS], w_reg[W_LOADS];
   auto load_global = [&](int kt) {
-    const int64_t k = (int64_t)kt * BK;
 #pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) a_reg[j] = ld_bf16x8(a_ptr[j] + k);
+    for (int j = 0; j < A_LOADS; ++j) a_reg[j] = ld_bf16x8(a_ptr[j] + (int64_t)kt * 2 * p.a_lay.kb);
 #pragma unroll
-    for (int j = 0; j < W_LOADS; ++j) w_reg[j] = ld_bf16x8(w_ptr + (int64_t)(32 * j) * p.Kpad + k);
+    for (int j = 0; j < W_LOADS; ++j) w_reg[j] = ld_bf16x8(w_ptr + (int64_t)(16 * j) * p.w_lay.pair + (int64_t)kt * 2 * p.w_lay.kb);
   };
   auto store_lds = [&](int buf) {
     bf16* a = sA + buf * BM * BK;
@@ -466,7 +471,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
     bf16x4 o;
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = (bf16)(silu_f(g[e]) * u[e]);
-    *reinterpret_cast<bf16x4*>(p.out + (int64_t)m * p.ldo + j) = o;
+    *reinterpret_cast<bf16x4*>(p.out + operand_offset(p.u_lay, m, j)) = o;
   } else {
     const f32x4 t = sum_at(j);
     float v[4] = {t[0], t[1], t[2], t[3]};
@@ -477,7 +482,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
 struct TileInfo {
   int bm, bn, lds_bytes, wg_per_cu;
 };
-static const TileInfo kTiles[9] = {
+static const TileInfo kTiles[11] = {
     {0, 0, 0, 0},
     {256, 256, 2 * (256 + 256) * 128, 1},
     {128, 128, 2 * (128 + 128) * 128, 2},
@@ -487,6 +492,8 @@ static const TileInfo kTiles[9] = {
     {256, 256, 2 * 512 * 128, 1},  // 6: direct-to-LDS, BK 64 x 2 stages, 8 waves, 4 of them load
     {256, 256, 2 * 512 * 128, 1},  // 7: direct-to-LDS, BK 64 x 2 stages, 4 waves
     {256, 256, 2 * 512 * 128, 1},  // 8: direct-to-LDS, BK 64 x 2 stages, 8 waves, every wave loads
+    {256, 256, 4 * 512 * 64, 1},   // 9: direct-to-LDS, BK 32 x 4 stages, 4 waves
+    {256, 256, 5 * 512 * 64, 1},   // 10: direct-to-LDS, BK 32 x 5 stages (all 160 KiB of LDS), 4 waves
 };
 
 hipError_t gemm_setup() {
@@ -514,13 +521,19 @@ hipError_t gemm_setup() {
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 2, 8>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[8].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 4, 4, 4, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[9].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 5, 4, 4, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[10].lds_bytes);
   return e;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   int t = a.force_tile;
-  if (t < 1 || t > 8) t = a.M <= 32 ? 4 : a.M <= 64 ? 3 : a.M <= 128 ? 2 : 8;
+  if (t < 1 || t > 10) t = a.M <= 32 ? 4 : a.M <= 64 ? 3 : a.M <= 128 ? 2 : 9;
   const TileInfo& ti = kTiles[t];
   GemmParams p;
   p.A = (const bf16*)a.A;
@@ -530,7 +543,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.out_f32 = a.epilogue == EPI_RESIDUAL ? a.out_f32 : 0;
   p.res_f32 = a.residual_f32;
   p.ws = a.workspace;
-  p.lda = a.lda;
+  p.a_lay = a.a_layout;
+  p.w_lay = layout_paired(a.Kpad);
+  p.u_lay = a.u_layout;
   p.Kpad = a.Kpad;
   p.Npad = a.Npad;
   p.ldo = a.ldo;
@@ -607,7 +622,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     case 5: gemm_dma_kernel<32, 4, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
     case 6: gemm_dma_kernel<64, 2, 4, 2, 4><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
     case 7: gemm_dma_kernel<64, 2, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    default: gemm_dma_kernel<64, 2, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 8: gemm_dma_kernel<64, 2, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 9: gemm_dma_kernel<32, 4, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    default: gemm_dma_kernel<32, 5, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -150,7 +150,7 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
     void* x_next = last ? hidden_out : (void*)((l & 1) ? st->xb : st->xa);
     {  // a1: pre-attention RMSNorm
       Timer t(st, s, T_NORM);
-      HIP_TRY(launch_rmsnorm(x, x_f32, d, st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
+      HIP_TRY(launch_rmsnorm(x, x_f32, d, st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, layout_paired(d), s));
     }
     GemmArgs g;
     memset(&g, 0, sizeof(g));
@@ -159,7 +159,7 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
     g.M = M;
     {  // a2: fused QKV projection
       Timer t(st, s, T_QKV);
-      g.A = st->y; g.lda = d;
+      g.A = st->y; g.a_layout = layout_paired(d);
       g.W = st->wqkv + (int64_t)l * st->Nqkv_pad * d; g.Kpad = d; g.Npad = st->Nqkv_pad;
       g.N_store = (int)st->Nqkv_pad; g.out = st->qkv; g.ldo = st->Nqkv_pad;
       g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE; g.out_f32 = 0; g.residual_f32 = 0;
@@ -175,14 +175,14 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
       if (ctx_lens)
         HIP_TRY(launch_attn_decode(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, ctx_lens, block_tables,
                                    c.max_pages_per_seq, st->attn_items, st->attn_n_items, st->part_o, st->part_ml,
-                                   st->max_chunks, span_len, st->attn, st->dq, s));
+                                   st->max_chunks, span_len, st->attn, layout_paired(st->dq), s));
       else
         HIP_TRY(launch_attn_prefill(st->qkv, st->Nqkv_pad, M, n_seqs, c.n_q_heads, kv, cu_seqlens, block_tables,
-                                    c.max_pages_per_seq, st->attn, st->dq, s));
+                                    c.max_pages_per_seq, st->attn, layout_paired(st->dq), s));
     }
     {  // a5: output projection + residual -> h (fp32)
       Timer t(st, s, T_O);
-      g.A = st->attn; g.lda = st->dq;
+      g.A = st->attn; g.a_layout = layout_paired(st->dq);
       g.W = st->wo + (int64_t)l * st->d_pad * st->dq; g.Kpad = st->dq; g.Npad = st->d_pad;
       g.N_store = (int)d; g.out = st->h; g.ldo = d; g.out_f32 = 1;
       g.residual = x; g.ldr = d; g.residual_f32 = x_f32; g.epilogue = EPI_RESIDUAL;
@@ -190,19 +190,19 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
     }
     {  // a6: pre-MLP RMSNorm
       Timer t(st, s, T_NORM);
-      HIP_TRY(launch_rmsnorm(st->h, 1, d, st->g_mlp + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, d, s));
+      HIP_TRY(launch_rmsnorm(st->h, 1, d, st->g_mlp + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, layout_paired(d), s));
     }
     {  // a7: gate/up projection + SwiGLU
       Timer t(st, s, T_GU);
-      g.A = st->y; g.lda = d;
+      g.A = st->y; g.a_layout = layout_paired(d);
       g.W = st->wgu + (int64_t)l * st->Ngu_pad * d; g.Kpad = d; g.Npad = st->Ngu_pad;
-      g.N_store = (int)st->Fpad; g.out = st->u; g.ldo = st->Fpad; g.out_f32 = 0;
+      g.N_store = (int)st->Fpad; g.out = st->u; g.ldo = st->Fpad; g.u_layout = layout_paired(st->Fpad); g.out_f32 = 0;
       g.residual = nullptr; g.ldr = 0; g.residual_f32 = 0; g.epilogue = EPI_SWIGLU;
       HIP_TRY(launch_gemm(g, s));
     }
     {  // a8: down projection + residual -> next layer's stream (fp32), or the stage output (bf16)
       Timer t(st, s, T_DOWN);
-      g.A = st->u; g.lda = st->Fpad;
+      g.A = st->u; g.a_layout = layout_paired(st->Fpad);
       g.W = st->wd + (int64_t)l * st->d_pad * st->Fpad; g.Kpad = st->Fpad; g.Npad = st->d_pad;
       g.N_store = (int)d; g.out = x_next; g.ldo = d; g.out_f32 = last ? 0 : 1;
       g.residual = st->h; g.ldr = d; g.residual_f32 = 1; g.epilogue = EPI_RESIDUAL;
@@ -254,7 +254,7 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
   A(&st->g_mlp, L * d, true);
   A(&st->kpool, L * st->pool_elems, true);
   A(&st->vpool, L * st->pool_elems, true);
-  const int64_t M = st->maxM;
+  const int64_t M = (st->maxM + 1) & ~1;  // row pairs: pair-interleaved activation buffers
   A(&st->y, M * d, true);
   A(&st->qkv, M * st->Nqkv_pad, true);
   A(&st->attn, M * st->dq, true);
@@ -438,7 +438,7 @@ int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out,
   if (M < 0 || N <= 0 || K <= 0) return fail(TDP_EINVAL, "bad GEMM shape");
   if (K % 64 || N % 4) return fail(TDP_EINVAL, "K must be a multiple of 64 and N of 4");
   if (epilogue != 0 && epilogue != 1) return fail(TDP_EINVAL, "epilogue must be 0 or 1");
-  if (tile < 0 || tile > 8 || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
+  if (tile < 0 || tile > 10 || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
   if (M == 0) return TDP_OK;
   if (!A || !W || !out || (epilogue == 1 && !residual)) return fail(TDP_EINVAL, "null pointer");
   hipStream_t s = (hipStream_t)stream;
@@ -454,7 +454,7 @@ int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out,
   if (e == hipSuccess) {
     GemmArgs g;
     memset(&g, 0, sizeof(g));
-    g.A = A; g.lda = K; g.W = wt; g.Kpad = K; g.Npad = Npad; g.M = M; g.N_store = N;
+    g.A = A; g.a_layout = layout_row_major(K); g.W = wt; g.Kpad = K; g.Npad = Npad; g.M = M; g.N_store = N;
     g.out = out; g.ldo = N; g.residual = residual; g.ldr = N;
     g.epilogue = epilogue ? EPI_RESIDUAL : EPI_STORE;
     g.workspace = ws; g.workspace_elems = ws_elems; g.force_tile = tile; g.force_splits = splits;

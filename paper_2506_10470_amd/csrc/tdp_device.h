@@ -39,6 +39,12 @@ __device__ __forceinline__ bf16x8 zero_bf16x8() {
   return z;
 }
 
+// Offset of element (r, k) in an operand laid out as (r>>1)*pair + (k>>5)*kb + (r&1)*par + (k&31).
+template <typename L>
+__device__ __forceinline__ int64_t operand_offset(const L& lay, int r, int k) {
+  return (int64_t)(r >> 1) * lay.pair + (int64_t)(k >> 5) * lay.kb + (int64_t)(r & 1) * lay.par + (k & 31);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

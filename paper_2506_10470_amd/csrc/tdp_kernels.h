@@ -5,6 +5,20 @@
 
 namespace tdp {
 
+// ---- operand layouts -----------------------------------------------------------------------------
+// Element (row r, column k) of a GEMM operand lives at
+//     (r >> 1) * pair + (k >> 5) * kb + (r & 1) * par + (k & 31)
+// Row-major with leading dimension ld:  pair = 2 ld, kb = 32, par = ld.
+// Pair-interleaved (rows 2p and 2p+1 alternate in 32-column blocks, so one 32-wide k step of a row
+// pair is one contiguous 128-byte line):  pair = 2 K, kb = 64, par = 32.  This is the layout of the
+// repacked weights and of the activations the stage's own kernels hand to the GEMMs: it lets a
+// k-stage of 32 be fetched with full-line requests.
+struct OperandLayout {
+  int64_t pair, kb, par;
+};
+static inline OperandLayout layout_row_major(int64_t ld) { return OperandLayout{2 * ld, 32, ld}; }
+static inline OperandLayout layout_paired(int64_t K) { return OperandLayout{2 * K, 64, 32}; }
+
 // ---- GEMM: out[M, N] = epilogue(A[M, K] * W^T), W stored [Npad][Kpad] (K contiguous) ---------
 enum Epilogue : int {
   EPI_STORE = 0,     // out = acc                        (QKV projection)
@@ -14,15 +28,16 @@ enum Epilogue : int {
 };
 
 struct GemmArgs {
-  const void* A;      // bf16 [M][lda]; rows >= M are never read
-  int64_t lda;
-  const void* W;      // bf16 [Npad][Kpad], zero padded
+  const void* A;      // bf16, M rows x Kpad columns in a_layout; rows >= M are never read
+  OperandLayout a_layout;
+  const void* W;      // bf16, Npad rows x Kpad columns, pair-interleaved, zero padded
   int64_t Kpad;       // multiple of 64
   int64_t Npad;       // multiple of 256
   int M;
   int N_store;        // columns of `out` that exist (SWIGLU: Npad/2 is stored up to N_store)
-  void* out;          // [M][ldo], bf16 unless out_f32
+  void* out;          // [M][ldo], bf16 unless out_f32; EPI_SWIGLU: bf16 in u_layout instead
   int64_t ldo;
+  OperandLayout u_layout;
   const void* residual;  // [M][ldr] or null, bf16 unless residual_f32
   int64_t ldr;
   int epilogue;
@@ -38,13 +53,14 @@ hipError_t gemm_setup();  // one-time function attributes (dynamic LDS size)
 
 // ---- weight repack: dst[row_of(n)][k] = src[k][n] -------------------------------------------
 // mode 0: row_of(n) = row_off + n;  mode 1: gate rows  (n/32)*64 + n%32;  mode 2: up rows (+32)
+// dst is pair-interleaved with Kpad = dst_ld columns
 hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in /*K*/, int64_t cols_out /*N*/,
                          void* dst, int64_t dst_ld, int64_t row_off, int mode, hipStream_t s);
 hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float* dst, hipStream_t s);
 
 // ---- RMSNorm ---------------------------------------------------------------------------------
 hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float* gain, float eps, int M, int d,
-                          void* y, int64_t ldy, hipStream_t s);
+                          void* y, OperandLayout y_layout, hipStream_t s);
 
 // ---- RoPE + KV append ------------------------------------------------------------------------
 struct KvLayout {
@@ -73,9 +89,9 @@ hipError_t launch_attn_plan(const int32_t* ctx_lens, int batch, int span_len, in
 hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
                               const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq,
                               const int2* items, const int32_t* n_items, float* part_o, float* part_ml,
-                              int max_spans, int span_len, void* out, int64_t ldo, hipStream_t s);
+                              int max_spans, int span_len, void* out, OperandLayout out_layout, hipStream_t s);
 hipError_t launch_attn_prefill(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
                                const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
-                               int max_pages_per_seq, void* out, int64_t ldo, hipStream_t s);
+                               int max_pages_per_seq, void* out, OperandLayout out_layout, hipStream_t s);
 
 }  // namespace tdp
