@@ -129,10 +129,12 @@ __device__ __forceinline__ bool gemm_tile_of_block(const GemmParams& p, int& til
   return tile_m < p.tiles_m && tile_n < p.tiles_n;
 }
 
-// 256 x 256 output tile fed by direct global->LDS loads (no staging registers).
+// BM x 256 output tile fed by direct global->LDS loads (no staging registers).
+//   BM      rows of the activation tile: 256 for prefill and large decode batches, 128 / 64 for
+//           small batches, where the GEMM only streams weights and more, smaller stages are better
 //   BK      k extent of one pipeline stage (64: 128-byte rows, 32: 64-byte rows)
 //   NS      stages resident in LDS; a stage's loads are issued NS-1 barriers before they are used
-//   TM, TN  32x32 MFMA tiles per wave along m / n; waves = (8/TM) x (8/TN)
+//   TM, TN  32x32 MFMA tiles per wave along m / n; waves = (BM/32/TM) x (8/TN)
 //   LOADERS waves that issue the global->LDS loads: all of them, or only the upper half (one per
 //           SIMD), so that while a loader wave is held up at load issue its SIMD-mate, which never
 //           touches the memory pipe, keeps the MFMA unit fed
@@ -141,18 +143,18 @@ __device__ __forceinline__ bool gemm_tile_of_block(const GemmParams& p, int& til
 // chunk c' ^ ((r / RW) % CPR) of that row (RW = rows per 256 bytes, CPR = 16-byte chunks per row).
 // With that swizzle the 16 lanes the LDS serves per cycle (16 consecutive rows of one logical
 // chunk) fall into 16 different 16-byte slots of the 64 banks: fragment reads are conflict free.
-template <int BK, int NS, int TM, int TN, int LOADERS>
-__global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(const GemmParams p) {
-  constexpr int BM = 256, BN = 256;
-  constexpr int WAVES_N = 8 / TN, WAVES = (8 / TM) * WAVES_N;
+template <int BM, int BK, int NS, int TM, int TN, int LOADERS>
+__global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_dma_kernel(const GemmParams p) {
+  constexpr int BN = 256;
+  constexpr int WAVES_N = 8 / TN, WAVES = (BM / (TM * 32)) * WAVES_N;
   constexpr int CPR = BK / 8;            // 16-byte chunks per row
   constexpr int RW = 256 / (BK * 2);     // rows per 256-byte bank window
   constexpr int RPI = 64 / CPR;          // rows per DMA instruction
   constexpr int KK = BK / 16;            // MFMA k-steps per stage
-  constexpr int IPO = (256 / RPI) / LOADERS;  // DMA instructions per loader wave per operand per stage
+  constexpr int IPA = (BM / RPI) / LOADERS;  // DMA instructions per loader wave per stage: activations
+  constexpr int IPW = (BN / RPI) / LOADERS;  //                                            weights
   static_assert(LOADERS == WAVES || LOADERS * 2 == WAVES, "all waves load, or the upper half");
-  static_assert(KK >= 2 && IPO % 2 == 0, "a stage's loads are issued in two halves");
-  constexpr int AHEAD = NS - 1;
+  static_assert(IPA >= 1 && (BM / RPI) % LOADERS == 0 && (BN / RPI) % LOADERS == 0, "row blocks divide among loaders");
   constexpr int STAGE = (BM + BN) * BK;  // elements per stage: A rows then W rows
   constexpr int SPT = 64 / BK;           // stages per 64-wide k-tile
   static_assert(TN % 2 == 0 && KK % 2 == 0, "gate/up pairing and fragment set parity");
@@ -175,38 +177,45 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
   if (kt_end > p.k_tiles_total * SPT) kt_end = p.k_tiles_total * SPT;
   const int n_stages = kt_end - kt_begin;
 
-  // DMA assignment: loader wave lw moves row blocks lw*IPO .. lw*IPO+IPO-1 (RPI rows each) of both
-  // operands.  Addresses are a wave-uniform 64-bit base (tile origin + k) plus a 32-bit per-lane offset.
+  // DMA assignment: loader wave lw moves row blocks lw*IPA .. (activations) and lw*IPW .. (weights),
+  // RPI rows each.  Addresses are a wave-uniform 64-bit base (tile origin + k) plus a 32-bit
+  // per-lane offset.
   const bool is_loader = wave >= WAVES - LOADERS;
   const int lw_id = is_loader ? wave - (WAVES - LOADERS) : 0;
   const int r_in = lane / CPR;
-  unsigned a_goff[IPO], w_goff[IPO];
+  unsigned a_goff[IPA], w_goff[IPW];
 #pragma unroll
-  for (int j = 0; j < IPO; ++j) {
-    const int row = (lw_id * IPO + j) * RPI + r_in;
+  for (int j = 0; j < IPA; ++j) {
+    const int row = (lw_id * IPA + j) * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);  // 16-byte chunk of the stage's k range
     int m = row;
     if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
     a_goff[j] = (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + (c_sw >> 2) * p.a_lay.kb + (c_sw & 3) * 8);
+  }
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    const int row = (lw_id * IPW + j) * RPI + r_in;
+    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
     w_goff[j] = (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + (c_sw >> 2) * p.w_lay.kb + (c_sw & 3) * 8);
   }
   constexpr int KB_PER_STAGE = BK / 32;
   const bf16* a_base = p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * KB_PER_STAGE * p.a_lay.kb;
   const bf16* w_base = p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * KB_PER_STAGE * p.w_lay.kb;
-  // t relative to kt_begin, clamped so the tail re-fetches the last stage; half 0 / 1 of the loads
-  auto dma_stage = [&](int t, int half) {
+  // t relative to kt_begin, clamped so the tail re-fetches the last stage (never read)
+  auto dma_stage = [&](int t) {
     const int tc = t < n_stages ? t : n_stages - 1;
     const bf16* ab = a_base + (int64_t)tc * KB_PER_STAGE * p.a_lay.kb;
     const bf16* wb = w_base + (int64_t)tc * KB_PER_STAGE * p.w_lay.kb;
-    bf16* la = smem + (t % NS) * STAGE + lw_id * IPO * RPI * BK;
-    bf16* lw = la + BM * BK;
+    bf16* la = smem + (t % NS) * STAGE + lw_id * IPA * RPI * BK;
+    bf16* lw = smem + (t % NS) * STAGE + BM * BK + lw_id * IPW * RPI * BK;
 #pragma unroll
-    for (int j = half * (IPO / 2); j < (half + 1) * (IPO / 2); ++j) {
+    for (int j = 0; j < IPA; ++j)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ab + a_goff[j]),
                                        (__attribute__((address_space(3))) void*)(la + j * RPI * BK), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < IPW; ++j)
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wb + w_goff[j]),
                                        (__attribute__((address_space(3))) void*)(lw + j * RPI * BK), 16, 0, 0);
-    }
   };
 
   f32x16 acc[TN][TM];
@@ -246,7 +255,7 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
 #pragma unroll
       for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[set][tn], af[set][tm], acc[tn][tm]);
   };
-  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_DMA = 2 * IPO;  // N_DMA per loader wave per stage
+  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_DMA = IPA + IPW;  // N_DMA per loader wave per stage
   // A plain s_barrier is used, not __syncthreads(): its release fence would wait for ALL
   // outstanding loads and defeat the prefetch distance.  vmcnt(PENDING) = this wave's loads of the
   // next stage have landed; lgkmcnt(0) = its LDS reads of the buffer refilled next are complete.
@@ -259,17 +268,11 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
   if (n_stages > 0) {
     if (is_loader) {
 #pragma unroll
-      for (int t = 0; t < NS - 1; ++t) {
-        dma_stage(t, 0);
-        dma_stage(t, 1);
-      }
+      for (int t = 0; t < NS - 1; ++t) dma_stage(t);
     }
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
     read_frags(0, 0, 0);
-    if (is_loader) {
-      dma_stage(NS - 1, 0);
-      dma_stage(NS - 1, 1);
-    }
+    if (is_loader) dma_stage(NS - 1);
   }
   for (int t = 0; t < n_stages; ++t) {
 #pragma unroll
@@ -277,10 +280,7 @@ __global__ __launch_bounds__((8 / TM) * (8 / TN) * 64) void gemm_dma_kernel(cons
       if (kk == KK - 1) {
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
         read_frags(t + 1, 0, 0);
-        if (is_loader) {
-          dma_stage(t + NS, 0);
-          dma_stage(t + NS, 1);
-        }
+        if (is_loader) dma_stage(t + NS);
       } else {
         read_frags(t, kk + 1, (kk + 1) & 1);
       }
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
 struct TileInfo {
   int bm, bn, lds_bytes, wg_per_cu;
 };
-static const TileInfo kTiles[11] = {
+static const TileInfo kTiles[13] = {
     {0, 0, 0, 0},
     {256, 256, 2 * (256 + 256) * 128, 1},
     {128, 128, 2 * (128 + 128) * 128, 2},
@@ -494,6 +494,8 @@ static const TileInfo kTiles[11] = {
     {256, 256, 2 * 512 * 128, 1},  // 8: direct-to-LDS, BK 64 x 2 stages, 8 waves, every wave loads
     {256, 256, 4 * 512 * 64, 1},   // 9: direct-to-LDS, BK 32 x 4 stages, 4 waves
     {256, 256, 5 * 512 * 64, 1},   // 10: direct-to-LDS, BK 32 x 5 stages (all 160 KiB of LDS), 4 waves
+    {128, 256, 6 * 384 * 64, 1},   // 11: direct-to-LDS, 128 x 256 tile, BK 32 x 6 stages, 4 waves
+    {64, 256, 4 * 320 * 64, 2},    // 12: direct-to-LDS, 64 x 256 tile, BK 32 x 4 stages, 4 waves
 };
 
 hipError_t gemm_setup() {
@@ -510,30 +512,36 @@ hipError_t gemm_setup() {
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<32, 256, 1, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[4].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 4, 4, 2, 8>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 32, 4, 4, 2, 8>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[5].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 2, 4>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 64, 2, 4, 2, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[6].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 4, 4>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 64, 2, 4, 4, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[7].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 2, 4, 2, 8>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 64, 2, 4, 2, 8>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[8].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 4, 4, 4, 4>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 32, 4, 4, 4, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[9].lds_bytes);
   if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<32, 5, 4, 4, 4>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 32, 5, 4, 4, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[10].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<128, 32, 6, 2, 4, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[11].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 32, 4, 2, 2, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[12].lds_bytes);
   return e;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   int t = a.force_tile;
-  if (t < 1 || t > 10) t = a.M <= 32 ? 4 : a.M <= 64 ? 3 : a.M <= 128 ? 2 : 9;
+  if (t < 1 || t > 12) t = a.M <= 32 ? 4 : a.M <= 128 ? 11 : 9;
   const TileInfo& ti = kTiles[t];
   GemmParams p;
   p.A = (const bf16*)a.A;
@@ -619,12 +627,14 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     case 2: gemm_kernel<128, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
     case 3: gemm_kernel<64, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
     case 4: gemm_kernel<32, 256, 1, 4><<<grid, block, ti.lds_bytes, s>>>(p); break;
-    case 5: gemm_dma_kernel<32, 4, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 6: gemm_dma_kernel<64, 2, 4, 2, 4><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 7: gemm_dma_kernel<64, 2, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 8: gemm_dma_kernel<64, 2, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 9: gemm_dma_kernel<32, 4, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    default: gemm_dma_kernel<32, 5, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 5: gemm_dma_kernel<256, 32, 4, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 6: gemm_dma_kernel<256, 64, 2, 4, 2, 4><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 7: gemm_dma_kernel<256, 64, 2, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 8: gemm_dma_kernel<256, 64, 2, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
+    case 9: gemm_dma_kernel<256, 32, 4, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 10: gemm_dma_kernel<256, 32, 5, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 11: gemm_dma_kernel<128, 32, 6, 2, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    default: gemm_dma_kernel<64, 32, 4, 2, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
