@@ -292,40 +292,69 @@ hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_he
 }
 
 // =====================================================================================
-// Prefill: one wave per (block of 32 query rows, query head); var-len packed, causal.
+// Prefill: var-len packed, causal.  One workgroup of eight waves per tile of 256 query columns that
+// share one K/V head: NH query heads of a GQA group x 256/NH consecutive positions (NH = 1 for
+// multi-head attention: 256 positions of one head); each wave owns 32 columns.  Each 32-token
+// block of K and V^T is staged once per workgroup in LDS (double buffered, XOR-swizzled against
+// bank conflicts) and feeds the MFMAs of all 256 columns, so K/V traffic per MFMA is 1/8 of a
+// wave-private scheme.  Two waves share a SIMD, so one wave's softmax arithmetic overlaps the
+// other's MFMAs; the softmax itself is trimmed to what a wave64 vector unit can keep up with:
+// one FMA + one raw exp2 per score, masking only in blocks that cross the diagonal or the end of
+// the prompt, and the running maximum is only raised (and the accumulator rescaled) when a
+// block's maximum exceeds it by more than 2^8, which keeps every probability below 256.
+// Same transposed-score trick as decode: S^T = K Q^T with score rows permuted so that a lane's
+// accumulator elements are the 8 consecutive tokens it supplies to O^T += V^T P^T.
 // =====================================================================================
-template <int DH>
-__global__ __launch_bounds__(64) void attn_prefill_kernel(const bf16* __restrict__ qkv, int64_t ld,
-                                                          int n_q_heads, KvLayout kv,
-                                                          const int32_t* __restrict__ cu_seqlens, int n_seqs,
-                                                          const int32_t* __restrict__ block_tables,
-                                                          int max_pages_per_seq, bf16* __restrict__ out,
-                                                          OperandLayout out_lay, float scale_log2) {
-  constexpr int KS = DH / 16;  // k-steps of the score MFMA
-  constexpr int DT = DH / 32;  // 32-channel tiles of the output
-  const int h = blockIdx.y;
-  // locate the sequence that owns query block blockIdx.x
-  int qb = blockIdx.x, s = 0, L = 0;
+constexpr float kRescaleSlack = 8.0f;  // log2 units
+
+template <int DH, int NH>
+__global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restrict__ qkv, int64_t ld,
+                                                           int n_q_heads, KvLayout kv,
+                                                           const int32_t* __restrict__ cu_seqlens, int n_seqs,
+                                                           const int32_t* __restrict__ block_tables,
+                                                           int max_pages_per_seq, bf16* __restrict__ out,
+                                                           OperandLayout out_lay, float scale_log2) {
+  constexpr int NP = 256 / NH;   // query positions per workgroup
+  constexpr int PB = NP / 32;    // 32-position blocks per head
+  constexpr int KS = DH / 16;    // k-steps of the score MFMA
+  constexpr int DT = DH / 32;    // 32-channel tiles of the output
+  constexpr int CR = DH / 8;     // 16-byte chunks per K row
+  constexpr int RWK = DH == 128 ? 1 : 2;  // K rows per 256-byte bank window
+  constexpr int NCHUNK = 32 * CR;         // chunks per block of K, and of V^T (DH * 4)
+  static_assert(NCHUNK <= 512, "one chunk of K and one of V^T per thread");
+  __shared__ __attribute__((aligned(16))) bf16 sK[2][32 * DH];
+  __shared__ __attribute__((aligned(16))) bf16 sV[2][DH * 32];
+
+  // locate the sequence that owns query tile blockIdx.x
+  int qt = blockIdx.x, s = 0, L = 0;
   for (; s < n_seqs; ++s) {
     L = cu_seqlens[s + 1] - cu_seqlens[s];
-    const int nb = (L + 31) >> 5;
-    if (qb < nb) break;
-    qb -= nb;
+    const int nt = (L + NP - 1) / NP;
+    if (qt < nt) break;
+    qt -= nt;
   }
   if (s == n_seqs) return;
   const int tok0 = cu_seqlens[s];
-  const int q0 = qb * 32;
+  const int q0 = qt * NP;
   const int Hkv = kv.n_kv_heads;
-  const int kvh = h / (n_q_heads / Hkv);
-  const int lane = threadIdx.x;
+  const int G = n_q_heads / Hkv;
+  const int groups = G / NH;
+  const int kvh = blockIdx.y / groups;
+  const int h_base = kvh * G + (blockIdx.y % groups) * NH;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, kg = lane >> 5;
   const bf16* kpool = (const bf16*)kv.k_pool;
   const bf16* vpool = (const bf16*)kv.v_pool;
-  const int qpos = q0 + l32;  // this lane's query column (may lie past the end of the prompt)
 
+  // the wave's 32 query columns: one head, 32 consecutive positions
+  const int head = h_base + wave / PB;
+  const int p_first = q0 + (wave % PB) * 32;
+  const int qpos = p_first + l32;  // may lie past the end of the prompt: computed, never stored
+  const int p_last = min(p_first + 31, L - 1);
   bf16x8 qf[KS];
   {
-    const bf16* qp = qkv + (int64_t)(tok0 + min(qpos, L - 1)) * ld + (int64_t)h * DH + kg * 8;
+    const bf16* qp = qkv + (int64_t)(tok0 + min(qpos, L - 1)) * ld + (int64_t)head * DH + kg * 8;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qf[kk] = ld_bf16x8(qp + kk * 16);
   }
@@ -338,62 +367,91 @@ __global__ __launch_bounds__(64) void attn_prefill_kernel(const bf16* __restrict
 
   const int32_t* bt = block_tables + (int64_t)s * max_pages_per_seq;
   const int last_page = (L - 1) / 16;
-  const int kv_end = min(q0 + 32, L);
+  const int kv_end = min(q0 + NP, L);
   // token of this lane's row r = l32 in the score tile: (r/16)*16 + ((r%8)/4)*8 + ((r/8)%2)*4 + r%4
   const int krow = (l32 >> 4) * 16 + ((l32 >> 2) & 1) * 8 + ((l32 >> 3) & 1) * 4 + (l32 & 3);
+  const bf16* k_frag = &sK[0][0] + krow * DH;
+  const int k_swz = (krow / RWK) % CR;
 
-  for (int kb = 0; kb < kv_end; kb += 32) {
+  // staging: this thread's chunk of K and of V^T of the next block
+  const bool stager = tid < NCHUNK;
+  const int k_tok = tid / CR, k_c = tid % CR;
+  const int v_r = tid >> 2, v_c = tid & 3;
+  bf16x8 kreg, vreg;
+  auto load_block = [&](int kb) {
+    if (!stager) return;
     const int p0 = kb >> 4;
-    const int p1 = min(p0 + 1, last_page);
+    const int p1 = min(p0 + 1, last_page);  // never dereference a table entry past the last page
     const int64_t page0 = bt[p0], page1 = bt[p1];
-    f32x16 sc;
+    kreg = ld_bf16x8(kpool + (((k_tok < 16 ? page0 : page1) * Hkv + kvh) * 16 + (k_tok & 15)) * DH + k_c * 8);
+    bf16x8 v = ld_bf16x8(vpool + (((v_c < 2 ? page0 : page1) * Hkv + kvh) * DH + v_r) * 16 + (v_c & 1) * 8);
+    if (kb + 32 > L) {  // slots past the prompt may hold anything, even NaN
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sc[i] = 0.f;
-    {
-      const int64_t page = krow < 16 ? page0 : page1;
-      const bf16* kp = kpool + ((page * Hkv + kvh) * 16 + (krow & 15)) * DH + kg * 8;
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) sc = mfma32(ld_bf16x8(kp + kk * 16), qf[kk], sc);
+      for (int e = 0; e < 8; ++e)
+        if (kb + v_c * 8 + e >= L) v[e] = (bf16)0.0f;
     }
-    // element i of this lane is token kb + (i/8)*16 + kg*8 + i%8 of query column qpos
-    float mx = kNegBig;
+    vreg = v;
+  };
+  auto store_block = [&](int buf) {
+    if (!stager) return;
+    st_bf16x8(&sK[buf][k_tok * DH + ((k_c ^ ((k_tok / RWK) % CR)) << 3)], kreg);
+    st_bf16x8(&sV[buf][v_r * 32 + ((v_c ^ ((v_r >> 2) & 3)) << 3)], vreg);
+  };
+
+  load_block(0);
+  store_block(0);
+  __syncthreads();
+  for (int kb = 0, buf = 0; kb < kv_end; kb += 32, buf ^= 1) {
+    const bool more = kb + 32 < kv_end;
+    if (more) load_block(kb + 32);
+    if (kb <= p_last && p_first < L) {  // causal: blocks past the wave's last row contribute nothing
+      f32x16 sc;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int tok = kb + (i >> 3) * 16 + kg * 8 + (i & 7);
-      const float v = (tok <= qpos && tok < L) ? sc[i] * scale_log2 : kNegBig;
-      sc[i] = v;
-      mx = fmaxf(mx, v);
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = exp2f(m - m_new);
-    bf16x8 pb[2];
-    float psum = 0.f;
+      for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float pv = exp2f(sc[i] - m_new);
-      psum += pv;
-      pb[i >> 3][i & 7] = (bf16)pv;
-    }
-    lsum = lsum * alpha + psum;
-    m = m_new;
-    const bool tail = kb + 32 > L;
+      for (int kk = 0; kk < KS; ++kk)
+        sc = mfma32(ld_bf16x8(k_frag + buf * 32 * DH + (((kk * 2 + kg) ^ k_swz) << 3)), qf[kk], sc);
+      // element i of this lane is token kb + (i/8)*16 + kg*8 + i%8 of query column qpos
+      if (kb + 31 > p_first || kb + 32 > L) {  // the block crosses the diagonal or the prompt's end
 #pragma unroll
-    for (int d = 0; d < DT; ++d) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
-#pragma unroll
-      for (int st = 0; st < 2; ++st) {
-        const int64_t page = st == 0 ? page0 : page1;
-        bf16x8 vf = ld_bf16x8(vpool + ((page * Hkv + kvh) * DH + d * 32 + l32) * 16 + kg * 8);
-        if (tail) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (kb + st * 16 + kg * 8 + j >= L) vf[j] = (bf16)0.0f;
+        for (int i = 0; i < 16; ++i) {
+          const int tok = kb + (i >> 3) * 16 + kg * 8 + (i & 7);
+          if (!(tok <= qpos && tok < L)) sc[i] = kNegBig;
         }
-        o[d] = mfma32(vf, pb[st], o[d]);
+      }
+      float mx = sc[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sc[i]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;  // scale > 0: max commutes with it
+      if (__any(mx > m + kRescaleSlack)) {
+        const float m_new = fmaxf(m, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        lsum *= alpha;
+        m = m_new;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[d][i] *= alpha;
+      }
+      bf16x8 pb[2];
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float pv = __builtin_amdgcn_exp2f(fmaf(sc[i], scale_log2, -m));
+        psum += pv;
+        pb[i >> 3][i & 7] = (bf16)pv;
+      }
+      lsum += psum;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        const int r = d * 32 + l32;
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+          o[d] = mfma32(ld_bf16x8(&sV[buf][r * 32 + (((st * 2 + kg) ^ ((r >> 2) & 3)) << 3)]), pb[st], o[d]);
       }
     }
+    if (more) store_block(buf ^ 1);
+    __syncthreads();
   }
   lsum += __shfl_xor(lsum, 32, 64);
   if (qpos < L) {
@@ -405,24 +463,46 @@ __global__ __launch_bounds__(64) void attn_prefill_kernel(const bf16* __restrict
         bf16x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[d][g * 4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(out + operand_offset(out_lay, tok0 + qpos, h * DH + d * 32 + g * 8 + kg * 4)) = v;
+        *reinterpret_cast<bf16x4*>(out + operand_offset(out_lay, tok0 + qpos, head * DH + d * 32 + g * 8 + kg * 4)) =
+            v;
       }
   }
+}
+
+template <int DH, int NH>
+static hipError_t launch_attn_prefill_t(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
+                                        const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
+                                        int max_pages_per_seq, void* out, OperandLayout out_layout, hipStream_t s) {
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
+  constexpr int NP = 256 / NH;
+  dim3 grid((total_tokens + NP - 1) / NP + n_seqs, n_q_heads / NH);
+  attn_prefill_kernel<DH, NH><<<grid, 512, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
+                                                   block_tables, max_pages_per_seq, (bf16*)out, out_layout,
+                                                   scale_log2);
+  return hipGetLastError();
 }
 
 hipError_t launch_attn_prefill(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
                                const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
                                int max_pages_per_seq, void* out, OperandLayout out_layout, hipStream_t s) {
   if (total_tokens <= 0 || n_seqs <= 0) return hipSuccess;
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
-  dim3 grid((total_tokens + 31) / 32 + n_seqs, n_q_heads);
-  if (kv.head_dim == 128)
-    attn_prefill_kernel<128><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
-                                                 block_tables, max_pages_per_seq, (bf16*)out, out_layout, scale_log2);
-  else
-    attn_prefill_kernel<64><<<grid, 64, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
-                                                block_tables, max_pages_per_seq, (bf16*)out, out_layout, scale_log2);
-  return hipGetLastError();
+  const int G = n_q_heads / kv.n_kv_heads;
+  const int nh = G % 8 == 0 ? 8 : G % 4 == 0 ? 4 : G % 2 == 0 ? 2 : 1;
+#define TDP_PREFILL(DH_, NH_)                                                                               \
+  return launch_attn_prefill_t<DH_, NH_>(qkv, ld, total_tokens, n_seqs, n_q_heads, kv, cu_seqlens, block_tables, \
+                                         max_pages_per_seq, out, out_layout, s)
+  if (kv.head_dim == 128) {
+    if (nh == 8) TDP_PREFILL(128, 8);
+    if (nh == 4) TDP_PREFILL(128, 4);
+    if (nh == 2) TDP_PREFILL(128, 2);
+    TDP_PREFILL(128, 1);
+  } else {
+    if (nh == 8) TDP_PREFILL(64, 8);
+    if (nh == 4) TDP_PREFILL(64, 4);
+    if (nh == 2) TDP_PREFILL(64, 2);
+    TDP_PREFILL(64, 1);
+  }
+#undef TDP_PREFILL
 }
 
 }  // namespace tdp

@@ -62,3 +62,10 @@ def test_gemm_entry_rejects_bad_shapes():
     # M = 0 is a no-op, and null pointers with M > 0 are rejected
     assert tdp.lib.tdp_gemm_bf16(None, None, None, None, 0, 64, 64, 0, 0, 0, None) == tdp.OK
     assert tdp.lib.tdp_gemm_bf16(None, None, None, None, 1, 64, 64, 0, 0, 0, None) == tdp.EINVAL
+
+
+def test_layer_range_and_timing_calls_reject_null_stage():
+    assert tdp.lib.tdp_stage_set_layer_range(None, 0, 1) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_timing_enable(None, 1) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_kv_import(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_kv_export(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL

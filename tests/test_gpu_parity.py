@@ -260,6 +260,30 @@ def test_empty_batches_are_no_ops_and_limits_are_enforced(tdp):
             tdp.tdp_stage_set_weight(st.h, 0, tdp.WQ, x, tdp.BF16, tdp.DEVICE, 3, 3)
 
 
+def test_layer_range_composes_to_the_whole_stage(tdp):
+    """Running layers [0,1) then [1,2) with a bf16 hand-over in between is a two-stage pipeline of
+    the same model: it must agree with the oracle like the one-stage run does, and the range must
+    be validated."""
+    sh = W.SHAPES["tiny_gqa"]
+    ctx = np.array([3, 40, 100, 17], dtype=np.int64)
+    batch = W.make_decode_batch(ctx)
+    with Stage(tdp, sh, batch.num_pages, 4, 0, 0, batch.tables.shape[1]) as st:
+        caches = import_kv(tdp, st, ctx, batch.tables, 8)
+        x = W.hidden_states(sh, 4, 8, device="cuda")
+        mid, out = torch.empty_like(x), torch.empty_like(x)
+        tdp.tdp_stage_set_layer_range(st.h, 0, 1)
+        tdp.tdp_stage_decode(st.h, x, i32(ctx), i32(batch.tables), 4, mid)
+        tdp.tdp_stage_set_layer_range(st.h, 1, 1)
+        tdp.tdp_stage_decode(st.h, mid, i32(ctx), i32(batch.tables), 4, out)
+        tdp.tdp_stage_set_layer_range(st.h, 0, 0)
+        torch.cuda.synchronize()
+        ref, _ = O.stage_decode(list(f64(x)), caches, list(oracle_layers(sh)), oracle_shape(sh))
+        assert row_rel_err(f64(out), np.stack(ref)) <= TOL
+        for first, count in ((-1, 1), (0, 3), (2, 1), (1, -1)):
+            with pytest.raises(tdp.TdpError):
+                tdp.tdp_stage_set_layer_range(st.h, first, count)
+
+
 def test_fp32_and_host_weights_are_rounded_like_bf16_weights(tdp):
     sh = W.SHAPES["tiny"]
     ctx = np.array([16, 40], dtype=np.int64)
