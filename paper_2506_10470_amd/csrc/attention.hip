@@ -320,10 +320,9 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
   constexpr int DT = DH / 32;    // 32-channel tiles of the output
   constexpr int CR = DH / 8;     // 16-byte chunks per K row
   constexpr int RWK = DH == 128 ? 1 : 2;  // K rows per 256-byte bank window
-  constexpr int NCHUNK = 32 * CR;         // chunks per block of K, and of V^T (DH * 4)
-  static_assert(NCHUNK <= 512, "one chunk of K and one of V^T per thread");
-  __shared__ __attribute__((aligned(16))) bf16 sK[2][32 * DH];
-  __shared__ __attribute__((aligned(16))) bf16 sV[2][DH * 32];
+  constexpr int NCH = CR / 8;    // chunks of K, and of V^T, per thread per 64-token block
+  __shared__ __attribute__((aligned(16))) bf16 sK[2][2][32 * DH];  // [buffer][32-token half]
+  __shared__ __attribute__((aligned(16))) bf16 sV[2][2][DH * 32];
 
   // locate the sequence that owns query tile blockIdx.x
   int qt = blockIdx.x, s = 0, L = 0;
@@ -370,47 +369,61 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
   const int kv_end = min(q0 + NP, L);
   // token of this lane's row r = l32 in the score tile: (r/16)*16 + ((r%8)/4)*8 + ((r/8)%2)*4 + r%4
   const int krow = (l32 >> 4) * 16 + ((l32 >> 2) & 1) * 8 + ((l32 >> 3) & 1) * 4 + (l32 & 3);
-  const bf16* k_frag = &sK[0][0] + krow * DH;
+  const bf16* k_frag = &sK[0][0][0] + krow * DH;
   const int k_swz = (krow / RWK) % CR;
 
-  // staging: this thread's chunk of K and of V^T of the next block
-  const bool stager = tid < NCHUNK;
-  const int k_tok = tid / CR, k_c = tid % CR;
-  const int v_r = tid >> 2, v_c = tid & 3;
-  bf16x8 kreg, vreg;
+  // staging: this thread's chunks of K and of V^T of the next 64-token block (two 32-token halves)
+  bf16x8 kreg[NCH], vreg[NCH];
   auto load_block = [&](int kb) {
-    if (!stager) return;
     const int p0 = kb >> 4;
-    const int p1 = min(p0 + 1, last_page);  // never dereference a table entry past the last page
-    const int64_t page0 = bt[p0], page1 = bt[p1];
-    kreg = ld_bf16x8(kpool + (((k_tok < 16 ? page0 : page1) * Hkv + kvh) * 16 + (k_tok & 15)) * DH + k_c * 8);
-    bf16x8 v = ld_bf16x8(vpool + (((v_c < 2 ? page0 : page1) * Hkv + kvh) * DH + v_r) * 16 + (v_c & 1) * 8);
-    if (kb + 32 > L) {  // slots past the prompt may hold anything, even NaN
+    int64_t page[4];  // never dereference a table entry past the last page
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (kb + v_c * 8 + e >= L) v[e] = (bf16)0.0f;
+    for (int i = 0; i < 4; ++i) page[i] = bt[min(p0 + i, last_page)];
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int ci = tid + 512 * j;
+      const int ksub = ci / (32 * CR), ktok = (ci / CR) % 32, kc = ci % CR;
+      const int64_t kp = ksub ? (ktok < 16 ? page[2] : page[3]) : (ktok < 16 ? page[0] : page[1]);
+      kreg[j] = ld_bf16x8(kpool + ((kp * Hkv + kvh) * 16 + (ktok & 15)) * DH + kc * 8);
+      const int vsub = ci / (DH * 4), vr = (ci >> 2) % DH, vc = ci & 3;
+      const int64_t vp = vsub ? (vc < 2 ? page[2] : page[3]) : (vc < 2 ? page[0] : page[1]);
+      bf16x8 v = ld_bf16x8(vpool + ((vp * Hkv + kvh) * DH + vr) * 16 + (vc & 1) * 8);
+      if (kb + 64 > L) {  // slots past the prompt may hold anything, even NaN
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (kb + vsub * 32 + vc * 8 + e >= L) v[e] = (bf16)0.0f;
+      }
+      vreg[j] = v;
     }
-    vreg = v;
   };
   auto store_block = [&](int buf) {
-    if (!stager) return;
-    st_bf16x8(&sK[buf][k_tok * DH + ((k_c ^ ((k_tok / RWK) % CR)) << 3)], kreg);
-    st_bf16x8(&sV[buf][v_r * 32 + ((v_c ^ ((v_r >> 2) & 3)) << 3)], vreg);
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int ci = tid + 512 * j;
+      const int ksub = ci / (32 * CR), ktok = (ci / CR) % 32, kc = ci % CR;
+      st_bf16x8(&sK[buf][ksub][ktok * DH + ((kc ^ ((ktok / RWK) % CR)) << 3)], kreg[j]);
+      const int vsub = ci / (DH * 4), vr = (ci >> 2) % DH, vc = ci & 3;
+      st_bf16x8(&sV[buf][vsub][vr * 32 + ((vc ^ ((vr >> 2) & 3)) << 3)], vreg[j]);
+    }
   };
 
   load_block(0);
   store_block(0);
   __syncthreads();
-  for (int kb = 0, buf = 0; kb < kv_end; kb += 32, buf ^= 1) {
-    const bool more = kb + 32 < kv_end;
-    if (more) load_block(kb + 32);
-    if (kb <= p_last && p_first < L) {  // causal: blocks past the wave's last row contribute nothing
+  for (int kb0 = 0, buf = 0; kb0 < kv_end; kb0 += 64, buf ^= 1) {
+    const bool more = kb0 + 64 < kv_end;
+    if (more) load_block(kb0 + 64);
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const int kb = kb0 + sub * 32;
+      // causal: blocks past the wave's last row contribute nothing
+      if (kb > p_last || p_first >= L) continue;
       f32x16 sc;
 #pragma unroll
       for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk)
-        sc = mfma32(ld_bf16x8(k_frag + buf * 32 * DH + (((kk * 2 + kg) ^ k_swz) << 3)), qf[kk], sc);
+        sc = mfma32(ld_bf16x8(k_frag + (buf * 2 + sub) * 32 * DH + (((kk * 2 + kg) ^ k_swz) << 3)), qf[kk], sc);
       // element i of this lane is token kb + (i/8)*16 + kg*8 + i%8 of query column qpos
       if (kb + 31 > p_first || kb + 32 > L) {  // the block crosses the diagonal or the prompt's end
 #pragma unroll
@@ -447,7 +460,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
         const int r = d * 32 + l32;
 #pragma unroll
         for (int st = 0; st < 2; ++st)
-          o[d] = mfma32(ld_bf16x8(&sV[buf][r * 32 + (((st * 2 + kg) ^ ((r >> 2) & 3)) << 3)]), pb[st], o[d]);
+          o[d] = mfma32(ld_bf16x8(&sV[buf][sub][r * 32 + (((st * 2 + kg) ^ ((r >> 2) & 3)) << 3)]), pb[st], o[d]);
       }
     }
     if (more) store_block(buf ^ 1);
