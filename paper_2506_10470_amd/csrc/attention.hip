@@ -12,6 +12,8 @@
 // the order that makes a lane's accumulator elements the 8 consecutive tokens it must supply as
 // the "B" operand of O^T[channel][q] += V^T[channel][token] P^T[token][q].
 #include "tdp_device.h"
+#include <stdlib.h>
+
 #include "tdp_kernels.h"
 
 namespace tdp {
@@ -28,30 +30,44 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf: exp2 gives exa
 // =====================================================================================
 
 // items[i] = (request, span index); n_items[0] = count.  One workgroup, any batch size.
+// Longest work first: all full spans, then the requests' last (partial) spans by quarter of
+// span_len, longest quarter first, so the workgroups that run at the end of the launch are short.
 __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restrict__ ctx_lens, int batch, int span_len,
                                                         int2* __restrict__ items, int32_t* __restrict__ n_items) {
-  __shared__ int part[256];
+  constexpr int NB = 5;  // class 0: full spans; 1..4: last span with > 3/4, > 1/2, > 1/4, > 0 of span_len
+  __shared__ int part[NB][256];
   const int tid = threadIdx.x;
   const int per = (batch + 255) / 256;
   const int b0 = tid * per, b1 = min(b0 + per, batch);
-  int cnt = 0;
-  for (int b = b0; b < b1; ++b) cnt += (ctx_lens[b] + span_len) / span_len;
-  part[tid] = cnt;
+  const int quarter = span_len / 4;
+  auto last_class = [&](int n_total, int n) {  // tokens in the last span: 1 .. span_len
+    const int rem = n_total - (n - 1) * span_len;
+    return 4 - min((rem - 1) / quarter, 3);
+  };
+  for (int c = 0; c < NB; ++c) part[c][tid] = 0;
+  for (int b = b0; b < b1; ++b) {
+    const int n_total = ctx_lens[b] + 1;
+    const int n = (n_total + span_len - 1) / span_len;
+    part[0][tid] += n - 1;
+    part[last_class(n_total, n)][tid] += 1;
+  }
   __syncthreads();
   if (tid == 0) {
     int acc = 0;
-    for (int i = 0; i < 256; ++i) {
-      const int c = part[i];
-      part[i] = acc;
-      acc += c;
-    }
+    for (int c = 0; c < NB; ++c)
+      for (int i = 0; i < 256; ++i) {
+        const int v = part[c][i];
+        part[c][i] = acc;
+        acc += v;
+      }
     n_items[0] = acc;
   }
   __syncthreads();
-  int pos = part[tid];
   for (int b = b0; b < b1; ++b) {
-    const int n = (ctx_lens[b] + span_len) / span_len;
-    for (int k = 0; k < n; ++k) items[pos++] = make_int2(b, k);
+    const int n_total = ctx_lens[b] + 1;
+    const int n = (n_total + span_len - 1) / span_len;
+    for (int k = 0; k < n - 1; ++k) items[part[0][tid]++] = make_int2(b, k);  // part[c][tid]: this thread's cursor
+    items[part[last_class(n_total, n)][tid]++] = make_int2(b, n - 1);
   }
 }
 
@@ -254,7 +270,13 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
 // Span length: long spans (fewer partials; most requests finish inside one workgroup) unless the
 // batch is so small that parallelism has to come from splitting each context.  Measured on the
 // 70B shape: 1024 beats 256 from batch 16 up.
-int attn_decode_span(int batch, int n_kv_heads) { return batch * n_kv_heads >= 128 ? kDecodeSpanMax : kDecodeSpanMin; }
+int attn_decode_span(int batch, int n_kv_heads) {
+  if (const char* e = getenv("TDP_ATTN_SPAN")) {  // tuning aid: 256, 512 or 1024
+    const int v = atoi(e);
+    if (v == 256 || v == 512 || v == 1024) return v;
+  }
+  return batch * n_kv_heads >= 128 ? kDecodeSpanMax : kDecodeSpanMin;
+}
 
 hipError_t launch_attn_plan(const int32_t* ctx_lens, int batch, int span_len, int2* items, int32_t* n_items,
                             hipStream_t s) {

@@ -111,6 +111,46 @@ __device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)
   }
 }
 
+// The same epilogue for 16x16 accumulator tiles: a lane holds, for each (wt, at), output columns
+// n..n+3 of row m, with m = row0 + at*16 + l16 and n = col0 + wt*16 + kq*4.  Gate and up rows
+// alternate in blocks of 32 weight rows, i.e. tiles wt, wt+1 (gate) pair with wt+2, wt+3 (up).
+template <int AT, int WT>
+__device__ __forceinline__ void gemm_epilogue16(const GemmParams& p, f32x4 (&acc)[WT][AT], int row0, int col0,
+                                                int l16, int kq, int split) {
+#pragma unroll
+  for (int at = 0; at < AT; ++at) {
+    const int m = row0 + at * 16 + l16;
+    if (m >= p.M) continue;
+    if (p.splits > 1) {
+      float* dst = p.ws + ((int64_t)split * p.M + m) * p.Npad;
+#pragma unroll
+      for (int wt = 0; wt < WT; ++wt) *reinterpret_cast<f32x4*>(dst + col0 + wt * 16 + kq * 4) = acc[wt][at];
+    } else if (p.epilogue == EPI_SWIGLU) {
+#pragma unroll
+      for (int wt = 0; wt < WT; wt += 4)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int j = (col0 + wt * 16) / 2 + h * 16 + kq * 4;
+          if (j < p.N_store) {
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16)(silu_f(acc[wt + h][at][e]) * acc[wt + h + 2][at][e]);
+            *reinterpret_cast<bf16x4*>(p.out + operand_offset(p.u_lay, m, j)) = o;
+          }
+        }
+    } else {
+#pragma unroll
+      for (int wt = 0; wt < WT; ++wt) {
+        const int n = col0 + wt * 16 + kq * 4;
+        if (n < p.N_store) {
+          float v[4] = {acc[wt][at][0], acc[wt][at][1], acc[wt][at][2], acc[wt][at][3]};
+          store_row4(p, m, n, v);
+        }
+      }
+    }
+  }
+}
+
 // Workgroup -> (tile_m, tile_n, split).  Workgroups are dealt round-robin to the 8 XCDs, each
 // with its own L2, so the workgroups an XCD runs at once are given one compact sb_m x sb_n block
 // of tiles: they then share sb_m activation panels and sb_n weight panels in that L2.  Super-blocks
@@ -293,7 +333,153 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_dma_ker
       }
     }
   }
+  // loads still in flight target LDS only; they must land before the workgroup's LDS is released
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   gemm_epilogue<TM, TN>(p, acc, m0 + wm0, n0 + wn0, l32, kg, split);
+}
+
+// The same pipeline on v_mfma_f32_16x16x32_bf16: a stage of 32 k is exactly one MFMA k-step, a wave
+// tile of (TM*32) x (TN*32) is (TM*2) x (TN*2) accumulators of four registers.  Operand bytes read
+// from LDS per flop are the same as with 32x32x16 tiles, but the accumulator traffic in the
+// register file is half, and on a power-limited part that buys clock: with random operands an
+// MFMA-only loop sustains 2.16 PFLOP/s with 16x16x32 against 1.89 with 32x32x16 (measured).
+// Fragments of stage t+1 are read under the MFMAs of stage t (two register sets, the stage loop
+// is unrolled by two); one barrier per stage, at its start.
+template <int BM, int NS, int TM, int TN>
+__global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_kernel(const GemmParams p) {
+  constexpr int BN = 256, BK = 32;
+  constexpr int WAVES_N = 8 / TN, WAVES = (BM / (TM * 32)) * WAVES_N;
+  constexpr int CPR = BK / 8;         // 16-byte chunks per row
+  constexpr int RW = 256 / (BK * 2);  // rows per 256-byte bank window
+  constexpr int RPI = 64 / CPR;       // rows per DMA instruction
+  constexpr int IPA = (BM / RPI) / WAVES, IPW = (BN / RPI) / WAVES;
+  static_assert(IPA >= 1 && (BM / RPI) % WAVES == 0 && (BN / RPI) % WAVES == 0, "row blocks divide among waves");
+  constexpr int STAGE = (BM + BN) * BK;
+  constexpr int AT = TM * 2, WT = TN * 2;  // 16-row tiles per wave
+  static_assert(WT % 4 == 0, "gate/up pairing");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);  // [NS][BM + BN][BK]
+
+  int tile_m, tile_n, split;
+  if (!gemm_tile_of_block(p, tile_m, tile_n, split)) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave / WAVES_N) * (TM * 32);
+  const int wn0 = (wave % WAVES_N) * (TN * 32);
+  const int l16 = lane & 15;
+  const int kq = lane >> 4;
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * BN;
+  const int kt_begin = split * p.k_tiles_per_split * 2;
+  int kt_end = kt_begin + p.k_tiles_per_split * 2;
+  if (kt_end > p.k_tiles_total * 2) kt_end = p.k_tiles_total * 2;
+  const int n_stages = kt_end - kt_begin;  // even: two stages per 64-wide k-tile
+
+  const int r_in = lane / CPR;
+  unsigned a_goff[IPA], w_goff;
+#pragma unroll
+  for (int j = 0; j < IPA; ++j) {
+    const int row = (wave * IPA + j) * RPI + r_in;
+    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
+    int m = row;
+    if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
+    a_goff[j] = (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + c_sw * 8);
+  }
+  // weight rows need no clamp: row block j of this wave lies j * RPI rows further on, and the
+  // swizzle term (row / RW) % CPR does not depend on j (RPI is a multiple of RW * CPR)
+  static_assert(RPI % (RW * CPR) == 0 && RPI % 2 == 0, "swizzle and row parity repeat per row block");
+  {
+    const int row = wave * IPW * RPI + r_in;
+    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
+    w_goff = (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + c_sw * 8);
+  }
+  const int64_t w_jstride = (int64_t)(RPI / 2) * p.w_lay.pair;
+  const bf16* a_base = p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * p.a_lay.kb;
+  const bf16* w_base = p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * p.w_lay.kb;
+  // DMA instruction j (0 .. N_DMA-1) of stage t: activations first, then weights
+  constexpr int N_DMA = IPA + IPW;
+  auto dma_one = [&](int t, int j) {
+    const int tc = t < n_stages ? t : n_stages - 1;  // the tail re-fetches the last stage (never read)
+    if (j < IPA) {
+      const bf16* ab = a_base + (int64_t)tc * p.a_lay.kb;
+      bf16* la = smem + (t % NS) * STAGE + wave * IPA * RPI * BK;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ab + a_goff[j]),
+                                       (__attribute__((address_space(3))) void*)(la + j * RPI * BK), 16, 0, 0);
+    } else {
+      const int jw = j - IPA;
+      const bf16* wb = w_base + (int64_t)tc * p.w_lay.kb;
+      bf16* lw = smem + (t % NS) * STAGE + BM * BK + wave * IPW * RPI * BK;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wb + jw * w_jstride + w_goff),
+                                       (__attribute__((address_space(3))) void*)(lw + jw * RPI * BK), 16, 0, 0);
+    }
+  };
+  auto dma_stage = [&](int t) {
+#pragma unroll
+    for (int j = 0; j < N_DMA; ++j) dma_one(t, j);
+  };
+
+  f32x4 acc[WT][AT];
+#pragma unroll
+  for (int wt = 0; wt < WT; ++wt)
+#pragma unroll
+    for (int at = 0; at < AT; ++at) acc[wt][at] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // fragment reads: lane (l16, kq) supplies row l16 of a 16-row tile, k = kq*8 .. +8 of the stage
+  // Tile wt / at lies 16 rows = 16 * BK elements further on and 16 is a multiple of RW * CPR, so
+  // the swizzle term is the lane's alone: one base per operand, the rest are immediate offsets.
+  static_assert(16 % (RW * CPR) == 0, "swizzle repeats every 16 rows");
+  const int swz = (kq ^ ((l16 / RW) % CPR)) << 3;
+  const int w_off = (BM + wn0 + l16) * BK + swz;
+  const int a_off = (wm0 + l16) * BK + swz;
+  bf16x8 wf[2][WT], af[2][AT];
+  constexpr int PENDING = (NS - 2) * N_DMA;
+  static_assert(WT == 8 && N_DMA <= WT && AT <= WT, "one weight tile, one DMA and at most one activation tile per MFMA group");
+  auto read_frags = [&](int t, int set) {
+    const bf16* base = smem + (t % NS) * STAGE;
+#pragma unroll
+    for (int wt = 0; wt < WT; ++wt) wf[set][wt] = ld_bf16x8(base + w_off + wt * 16 * BK);
+#pragma unroll
+    for (int at = 0; at < AT; ++at) af[set][at] = ld_bf16x8(base + a_off + at * 16 * BK);
+  };
+  // Stage t: its fragments are in register set `set`; stage t+1 was requested NS-2 barriers ago.
+  // The MFMAs are inline assembly so that every accumulator stays in place in its AGPRs (left to
+  // itself the register allocator shuttles the 64 accumulator tuples through VGPRs); issue order
+  // is therefore explicit: eight groups of [fragment reads and one DMA of the stages ahead, the
+  // MFMAs of one weight tile], separated by scheduling barriers.
+  auto stage = [&](int t, int set) {
+    // vmcnt: this wave's loads of stage t+1 have landed; lgkmcnt: its reads of stage t are complete,
+    // so after the barrier buffer t % NS may be refilled and stage t+1 may be read
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+    const bf16* next = smem + ((t + 1) % NS) * STAGE;
+#pragma unroll
+    for (int g = 0; g < WT; ++g) {
+      wf[set ^ 1][g] = ld_bf16x8(next + w_off + g * 16 * BK);
+      if (g < AT) af[set ^ 1][g] = ld_bf16x8(next + a_off + g * 16 * BK);
+      if (g < N_DMA) dma_one(t + NS, g);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int at = 0; at < AT; ++at)
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[g][at]) : "v"(wf[set][g]), "v"(af[set][at]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  if (n_stages > 0) {
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t) dma_stage(t);
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+    read_frags(0, 0);
+    dma_stage(NS - 1);
+  }
+  for (int t = 0; t < n_stages; t += 2) {
+    stage(t, 0);
+    stage(t + 1, 1);
+  }
+  // loads still in flight target LDS only; they must land before the workgroup's LDS is released.
+  // The nops cover the MFMA -> accumulator-read distance, which the compiler cannot see.
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  gemm_epilogue16<AT, WT>(p, acc, m0 + wm0, n0 + wn0, l16, kq, split);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
@@ -482,7 +668,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
 struct TileInfo {
   int bm, bn, lds_bytes, wg_per_cu;
 };
-static const TileInfo kTiles[13] = {
+static const TileInfo kTiles[16] = {
     {0, 0, 0, 0},
     {256, 256, 2 * (256 + 256) * 128, 1},
     {128, 128, 2 * (128 + 128) * 128, 2},
@@ -496,6 +682,9 @@ static const TileInfo kTiles[13] = {
     {256, 256, 5 * 512 * 64, 1},   // 10: direct-to-LDS, BK 32 x 5 stages (all 160 KiB of LDS), 4 waves
     {128, 256, 6 * 384 * 64, 1},   // 11: direct-to-LDS, 128 x 256 tile, BK 32 x 6 stages, 4 waves
     {64, 256, 4 * 320 * 64, 2},    // 12: direct-to-LDS, 64 x 256 tile, BK 32 x 4 stages, 4 waves
+    {256, 256, 4 * 512 * 64, 1},   // 13: as 9 on 16x16x32 MFMA tiles
+    {128, 256, 6 * 384 * 64, 1},   // 14: as 11 on 16x16x32 MFMA tiles
+    {256, 256, 5 * 512 * 64, 1},   // 15: as 10 on 16x16x32 MFMA tiles
 };
 
 hipError_t gemm_setup() {
@@ -535,13 +724,22 @@ hipError_t gemm_setup() {
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 32, 4, 2, 2, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[12].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<256, 4, 4, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[13].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<128, 6, 2, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[14].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<256, 5, 4, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[15].lds_bytes);
   return e;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   int t = a.force_tile;
-  if (t < 1 || t > 12) t = a.M <= 32 ? 4 : a.M <= 128 ? 11 : 9;
+  if (t < 1 || t > 15) t = a.M <= 32 ? 4 : a.M <= 128 ? 14 : 13;
   const TileInfo& ti = kTiles[t];
   GemmParams p;
   p.A = (const bf16*)a.A;
@@ -634,7 +832,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     case 9: gemm_dma_kernel<256, 32, 4, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
     case 10: gemm_dma_kernel<256, 32, 5, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
     case 11: gemm_dma_kernel<128, 32, 6, 2, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    default: gemm_dma_kernel<64, 32, 4, 2, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 12: gemm_dma_kernel<64, 32, 4, 2, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 13: gemm_mi16_kernel<256, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 14: gemm_mi16_kernel<128, 6, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    default: gemm_mi16_kernel<256, 5, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
