@@ -181,6 +181,40 @@ def cpu_baseline(shape, dec_ctx, cu, budget_layers=4, n_requests=64):
                           float(np.mean([dec_ctx[b] for b in sample])), budget_layers, shape.n_layers, dt, t_prep)}
 
 
+def scheduler_section(shape, decode_sweep, prefill_curve, n_requests=20000, n_stages=4):
+    """The paper's three scheduling decisions (Sec. 3.3 - 3.5) driving a simulated pipeline of
+    `n_stages` copies of this stage, timed by the profile measured above: 20000 synthetic requests
+    (enough to fill the KV capacity several times over),
+    KV capacity = what 90 % of one GPU's 288 GB leaves after the stage's weights.  Host code only."""
+    from harness import workload as W
+    from paper_2506_10470_amd import accounting as A
+    from paper_2506_10470_amd import tdp_sched as L
+
+    dec = [(float(s["batch"]), float(s["ms_per_step"])) for s in decode_sweep]
+    pre = [(float(c["tokens"]), float(c["ms"])) for c in prefill_curve]
+    weights = 2 * shape.n_layers * A.matmul_params_per_layer(shape.d_model, shape.n_q_heads, shape.n_kv_heads,
+                                                             shape.head_dim, shape.d_ff)
+    kv_tok = A.kv_bytes_per_token(shape.n_layers, shape.n_kv_heads, shape.head_dim)
+    capacity = int((0.9 * 288e9 - weights) // kv_tok)
+    reqs = [tuple(int(v) for v in r) for r in W.serving_requests(n_requests)]
+    out = {}
+    names = {"td_pipe": (1, 1, 1), "no_greedy_prefill": (0, 1, 1), "no_work_stealing": (1, 0, 1),
+             "no_intensity_switch": (1, 1, 0), "none": (0, 0, 0)}
+    for name, (g, w, i) in names.items():
+        cfg = L.SimConfig(n_stages, capacity, 16384, g, w, i, 1)
+        t0 = time.perf_counter()
+        res, _ = L.tdp_simulate(cfg, reqs, dec, pre)
+        wall = time.perf_counter() - t0
+        out[name] = {"tok_s": round(res.generated_tokens / (res.total_ms * 1e-3), 1),
+                     "total_s": round(res.total_ms * 1e-3, 2), "phase_switches": res.phase_switches,
+                     "recomputes": res.recomputes, "peak_kv_tokens": res.peak_kv_tokens,
+                     "bubble_ratio": round(1.0 - res.busy_ms / (n_stages * res.total_ms), 4),
+                     "decisions": res.n_events, "scheduler_wall_ms": round(wall * 1e3, 2)}
+    return {"n_stages": n_stages, "n_requests": n_requests, "kv_capacity_tokens": capacity,
+            "prefill_token_budget": 16384, "data": "synthetic request lengths; stage times measured in this run",
+            "policies": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -311,10 +345,24 @@ def main():
                              "class_ms": {k: round(v, 3) for k, v in ctp.items()}, "kernels": kp}
         log("prefill T=%d: %.1f ms, %.0f tok/s, %.0f TFLOP/s (GEMMs %.0f TFLOP/s)" % (
             T, msp, T / msp * 1e3, wp["flops"] / msp / 1e9, wp["gemm_flops"] / gemm_ms / 1e9))
+        # prefill time against packed tokens (first k prompts): the profile the scheduler plans with
+        curve = []
+        for k in (1, 2, 4, 8):
+            if k >= len(pre_lens):
+                continue
+            Tk = int(pre.cu_seqlens[k])
+            msk = time_calls(lambda: tdp.tdp_stage_prefill(st.h, xp, cu_p, tab_p, k, Tk, op, stream), 1, 2)
+            curve.append({"tokens": Tk, "ms": round(msk, 3)})
+        curve.append({"tokens": T, "ms": round(msp, 3)})
+        result["prefill"]["curve"] = sorted(curve, key=lambda c: c["tokens"])
         del xp, op
 
     st.close()
     torch.cuda.empty_cache()
+    if "decode_sweep" in result and "prefill" in result:
+        result["scheduler"] = scheduler_section(shape, result["decode_sweep"], result["prefill"]["curve"])
+        log("scheduler (simulated 4-stage pipeline on the measured profile): %s" % json.dumps(
+            {k: v["tok_s"] for k, v in result["scheduler"]["policies"].items()}))
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(shape, dec_ctx, cu)
         log("cpu oracle: %s tok/s (%s)" % (result["cpu_baseline"]["value"], result["cpu_baseline"]["sample"]))

@@ -295,6 +295,20 @@ def prefill_seq_lens(config: str, n_seqs: int, seed: int = BASE_SEED) -> np.ndar
     raise KeyError(config)
 
 
+def serving_requests(n: int, seed: int = BASE_SEED) -> np.ndarray:
+    """Offline serving workload for the scheduler: int32 [n, 3] = (input length, output length,
+    predicted output length).  Stands in for the conversation dataset of the paper's throughput
+    runs (Sec. 4.1: prompts shorter than 1024 tokens, outputs from the model), which is not
+    available: prompts ~ LN(median 160, sigma 1.0) clipped to [4, 1023], outputs ~ LN(median 180,
+    sigma 0.9) clipped to [1, 1024]; the prediction is the output length times LN(1, 0.35), the
+    error of a coarse length classifier."""
+    ins = lognormal_lengths(stream_key(seed, 21, n), n, 160, 1.0, 4, 1023)
+    outs = lognormal_lengths(stream_key(seed, 22, n), n, 180, 0.9, 1, 1024)
+    noise = lognormal_lengths(stream_key(seed, 23, n), n, 1000, 0.35, 1, 10 ** 6).astype(np.float64) / 1000.0
+    pred = np.clip(np.rint(outs * noise), 1, 2048)
+    return np.stack([ins, outs, pred], axis=1).astype(np.int32)
+
+
 def make_decode_batch(ctx_lens: np.ndarray, page_size: int = PAGE_SIZE, seed: int = BASE_SEED,
                       max_pages_per_seq: int | None = None) -> DecodeBatch:
     """Pages are reserved for ctx+1 tokens: the step appends one token."""

@@ -1,4 +1,5 @@
-"""Compile the HIP sources into paper_2506_10470_amd/libtdp.so (gfx950 only).
+"""Compile the HIP sources into paper_2506_10470_amd/libtdp.so (gfx950 only) and the host-only
+scheduler into paper_2506_10470_amd/libtdp_sched.so.
 
 hipcc cross-compiles without a GPU.  Objects go to paper_2506_10470_amd/_build/ (git-ignored);
 the shared library stays in-tree so that it travels with the source tree.
@@ -14,6 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtdp.so")
+SCHED_LIB = os.path.join(HERE, "libtdp_sched.so")
 SOURCES = ("gemm.hip", "attention.hip", "elementwise.hip", "stage.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -42,8 +44,12 @@ def build(verbose: bool = False) -> str:
     with ThreadPoolExecutor(max_workers=4) as ex:
         list(ex.map(_run, jobs))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB])
+    cxx = os.environ.get("CXX", "g++")
+    _run([cxx, "-O2", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden", "-Wall", "-Wextra",
+          os.path.join(CSRC, "sched.cpp"), "-o", SCHED_LIB])
     if verbose:
         print("built", LIB)
+        print("built", SCHED_LIB)
     return LIB
 
 
