@@ -314,3 +314,47 @@ def test_layer_matches_library_composition_in_torch_fp64():
     y2 = rms(h, w.g_mlp)
     want = h + (torch.nn.functional.silu(y2 @ T(w.wg)) * (y2 @ T(w.wu))) @ T(w.wd)
     assert np.allclose(got, want.numpy(), atol=1e-11)
+
+
+# ---------------------------------------------------------------- pipeline ends
+
+def test_embedding_lookup_equals_one_hot_product():
+    from oracle import ends_oracle as E
+    rng = np.random.default_rng(31)
+    table = rng.standard_normal((50, 16))
+    ids = rng.integers(0, 50, size=23)
+    one_hot = np.zeros((23, 50))
+    one_hot[np.arange(23), ids] = 1.0
+    assert np.array_equal(E.embed(ids, table), one_hot @ table)
+    with pytest.raises(IndexError):
+        E.embed([50], table)
+    with pytest.raises(IndexError):
+        E.embed([-1], table)
+
+
+def test_greedy_takes_the_lowest_index_among_the_maxima():
+    from oracle import ends_oracle as E
+    assert list(E.greedy_tokens(np.array([[1.0, 3.0, 3.0, 2.0], [5.0, 5.0, 5.0, 5.0], [0.0, -1.0, 2.0, 2.0]]))) == [1, 0, 2]
+    rng = np.random.default_rng(32)
+    logits = rng.integers(0, 6, size=(40, 97)).astype(np.float64)      # many ties
+    assert np.array_equal(E.greedy_tokens(logits), np.argmax(logits, axis=1))
+    assert list(E.greedy_tokens(np.array([[-np.inf, -3.0, -np.inf]]))) == [1]
+
+
+def test_final_logits_closed_forms():
+    from oracle import ends_oracle as E
+    rng = np.random.default_rng(33)
+    x = rng.standard_normal((7, 12))
+    ones = np.ones(12)
+    # identity head, unit gain, eps -> 0: logits are x scaled to unit mean square, so the argmax is x's
+    lg = E.final_logits(x, ones, np.eye(12), 0.0)
+    assert np.allclose(np.mean(lg ** 2, axis=1), 1.0)
+    assert np.array_equal(E.greedy_tokens(lg), np.argmax(x, axis=1))
+    # the norm removes positive scale
+    w = rng.standard_normal((12, 30))
+    g = 1.0 + 0.1 * rng.standard_normal(12)
+    assert np.allclose(E.final_logits(3.7 * x, g, w, 0.0), E.final_logits(x, g, w, 0.0))
+    # the gain acts per input channel: folding it into the head's rows gives the same logits
+    assert np.allclose(E.final_logits(x, g, w, 1e-5), E.final_logits(x, ones, g[:, None] * w, 1e-5))
+    # a dropped norm would fail this: logits of a huge input stay bounded
+    assert np.max(np.abs(E.final_logits(1e6 * x, ones, w, 1e-5))) < 1e3
