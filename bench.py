@@ -181,6 +181,31 @@ def cpu_baseline(shape, dec_ctx, cu, budget_layers=4, n_requests=64):
                           float(np.mean([dec_ctx[b] for b in sample])), budget_layers, shape.n_layers, dt, t_prep)}
 
 
+def ends_section(tdp, W, shape, batch, i32, vocab=32000):
+    """What the first and the last stage of a pipeline add per decode step: the token-embedding
+    lookup, and final RMSNorm + vocabulary projection (fp32 logits) + greedy selection."""
+    import torch
+    h = tdp.tdp_ends_create(tdp.EndsConfig(vocab, shape.d_model, shape.rms_eps, batch))
+    for which, name, dt, rows, cols in ((tdp.E_EMBEDDING, "embedding", tdp.BF16, vocab, shape.d_model),
+                                        (tdp.E_LM_HEAD, "lm_head", tdp.BF16, shape.d_model, vocab),
+                                        (tdp.E_FINAL_NORM, "final_norm", tdp.F32, shape.d_model, 1)):
+        w = W.ends_weight(shape, name, vocab, device="cuda", dtype=torch.float32 if dt == tdp.F32 else torch.bfloat16)
+        tdp.tdp_ends_set_weight(h, which, w, dt, tdp.DEVICE, rows, cols)
+        del w
+    ids = i32(W.token_ids(vocab, batch, 1))
+    x = torch.empty((batch, shape.d_model), dtype=torch.bfloat16, device="cuda")
+    tok = torch.empty(batch, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+    t_embed = time_calls(lambda: tdp.tdp_embed_tokens(h, ids, batch, x, stream), 3, 20)
+    x = W.hidden_states(shape, batch, 5, device="cuda")
+    t_head = time_calls(lambda: tdp.tdp_lm_head(h, x, batch, None, batch, None, tok, stream), 3, 20)
+    tdp.tdp_ends_destroy(h)
+    flops = 2.0 * batch * vocab * shape.d_model
+    return {"vocab": vocab, "batch": batch, "embed_ms": round(t_embed, 4), "lm_head_ms": round(t_head, 4),
+            "lm_head_tflops": round(flops / t_head / 1e9, 1),
+            "lm_head_weight_gbs": round(vocab * shape.d_model * 2 / t_head / 1e6, 1)}
+
+
 def scheduler_section(shape, decode_sweep, prefill_curve, n_requests=20000, n_stages=4):
     """The paper's three scheduling decisions (Sec. 3.3 - 3.5) driving a simulated pipeline of
     `n_stages` copies of this stage, timed by the profile measured above: 20000 synthetic requests
@@ -359,6 +384,10 @@ def main():
 
     st.close()
     torch.cuda.empty_cache()
+    if not args.layers:
+        result["ends"] = ends_section(tdp, W, shape, B, i32)
+        log("pipeline ends at batch %d: embedding %.3f ms, final norm + vocabulary projection + greedy %.3f ms" % (
+            B, result["ends"]["embed_ms"], result["ends"]["lm_head_ms"]))
     if "decode_sweep" in result and "prefill" in result:
         result["scheduler"] = scheduler_section(shape, result["decode_sweep"], result["prefill"]["curve"])
         log("scheduler (simulated 4-stage pipeline on the measured profile): %s" % json.dumps(

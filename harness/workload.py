@@ -186,6 +186,26 @@ def hidden_states(sh: StageShape, n_tokens: int, stream: int, device="cpu",
     return normal_tensor(key, (n_tokens, sh.d_model), 1.0, 0.0, device, dtype)
 
 
+def ends_weight(sh: StageShape, which: str, vocab: int, device="cpu", dtype=torch.bfloat16,
+                seed: int = BASE_SEED) -> torch.Tensor:
+    """Weights of the pipeline ends: "embedding" [vocab, d] ~ N(0, 1) (so that embedded tokens look
+    like the N(0, 1) hidden states the stage is fed elsewhere), "lm_head" [d, vocab] ~ N(0, 0.02),
+    "final_norm" [d] ~ 1 + N(0, 0.02)."""
+    idx = {"embedding": 0, "lm_head": 1, "final_norm": 2}[which]
+    key = stream_key(seed, 1000 * sh.config_index, 4, idx, vocab)
+    if which == "embedding":
+        return normal_tensor(key, (vocab, sh.d_model), 1.0, 0.0, device, dtype)
+    if which == "lm_head":
+        return normal_tensor(key, (sh.d_model, vocab), 0.02, 0.0, device, dtype)
+    return normal_tensor(key, (sh.d_model,), 0.02, 1.0, device, dtype)
+
+
+def token_ids(vocab: int, n: int, stream: int, seed: int = BASE_SEED) -> np.ndarray:
+    """n token ids uniform in [0, vocab)."""
+    u = _uniform01(stream_key(seed, 5, stream, vocab), n)
+    return np.minimum((u * vocab).astype(np.int64), vocab - 1).astype(np.int32)
+
+
 def kv_packed(sh: StageShape, layer: int, which: str, total_tokens: int, stream: int,
               device="cpu", dtype=torch.bfloat16, seed: int = BASE_SEED,
               tok0: int = 0, toks: int | None = None) -> torch.Tensor:

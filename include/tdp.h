@@ -182,6 +182,42 @@ TDP_API int tdp_gemm_bf16(const void* A, const void* W, const void* residual, vo
 TDP_API int tdp_stage_timing_enable(tdp_stage* st, int32_t on);
 TDP_API int tdp_stage_timing_read(tdp_stage* st, float* ms /* host [7] */);
 
+/* ---- the two ends of the pipeline ---------------------------------------------------------------
+ * What runs in front of the first stage and behind the last one so that a chain of stages turns
+ * token ids into token ids (the paper measures generated tokens per second on whole models, Sec.
+ * 4.1 and Table 2): the token-embedding lookup, and the final RMSNorm + vocabulary projection +
+ * greedy selection.  A tdp_ends owns the embedding table (bf16 [vocab, d_model]), the final norm
+ * gain (fp32) and the vocabulary projection (bf16, repacked once), plus scratch for max_tokens rows.
+ * vocab_size must be a multiple of 4, d_model a multiple of 64. */
+typedef struct tdp_ends tdp_ends;
+typedef struct {
+  int32_t vocab_size, d_model;
+  float rms_eps;
+  int32_t max_tokens; /* rows per call */
+} tdp_ends_config;
+#define TDP_E_EMBEDDING 0  /* [vocab_size, d_model] */
+#define TDP_E_FINAL_NORM 1 /* [d_model, 1] */
+#define TDP_E_LM_HEAD 2    /* [d_model, vocab_size] row-major ([in, out] like every projection) */
+TDP_API int tdp_ends_create(const tdp_ends_config* cfg, tdp_ends** out);
+TDP_API void tdp_ends_destroy(tdp_ends* e);
+/* src: host or device (mem), fp32 or bf16 (dtype); synchronous */
+TDP_API int tdp_ends_set_weight(tdp_ends* e, int32_t which, const void* src, int32_t dtype, int32_t mem,
+                                int64_t rows, int64_t cols);
+/* hidden_out[m][:] = embedding[token_ids[m]][:].  token_ids dev int32 [M]; hidden_out dev bf16
+ * [M, d_model].  An id outside the vocabulary is clamped into it (never a wild read).  Enqueues on
+ * stream and returns. */
+TDP_API int tdp_embed_tokens(tdp_ends* e, const int32_t* token_ids, int32_t M, void* hidden_out, void* stream);
+/* For row m: x = hidden_in[row_index ? row_index[m] : m]; logits[m] = RMSNorm(x; gain) * W_head;
+ * next_token[m] = the lowest index among the largest logits.  hidden_in dev bf16 [n_rows_in,
+ * d_model]; row_index dev int32 [M] or null (prefill: the last token of each prompt), entries are
+ * clamped to [0, n_rows_in); logits_out dev fp32 [M, vocab_size] or null (internal scratch);
+ * next_token dev int32 [M] or null.  M <= max_tokens.  fp32 accumulation, fp32 logits. */
+TDP_API int tdp_lm_head(tdp_ends* e, const void* hidden_in, int32_t n_rows_in, const int32_t* row_index, int32_t M,
+                        float* logits_out, int32_t* next_token, void* stream);
+/* Greedy selection alone: out[m] = lowest index among the maxima of logits[m][0..n), rows ld apart.
+ * All device pointers.  NaN entries never win; a row of NaNs gives 0. */
+TDP_API int tdp_argmax_rows(const float* logits, int32_t M, int32_t n, int64_t ld, int32_t* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -245,4 +245,77 @@ hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float*
   return hipGetLastError();
 }
 
+// ---- pipeline ends: row gather (token embedding; last-token selection), bf16 conversion, argmax ----
+
+// dst[m][:] = src[idx[m]][:]; one workgroup per row, 16-byte pieces.  An index outside
+// [0, n_src_rows) is clamped into range, so a bad id can never read outside the table.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const bf16* __restrict__ src, int64_t ld_src,
+                                                          int64_t n_src_rows, const int32_t* __restrict__ idx,
+                                                          int d, bf16* __restrict__ dst, int64_t ld_dst) {
+  const int m = blockIdx.x;
+  int64_t r = idx[m];
+  r = r < 0 ? 0 : (r >= n_src_rows ? n_src_rows - 1 : r);
+  const bf16* sp = src + r * ld_src;
+  bf16* dp = dst + (int64_t)m * ld_dst;
+  for (int c = threadIdx.x * 8; c < d; c += 256 * 8) st_bf16x8(dp + c, ld_bf16x8(sp + c));
+}
+
+hipError_t launch_gather_rows(const void* src, int64_t ld_src, int64_t n_src_rows, const int32_t* idx, int M, int d,
+                              void* dst, int64_t ld_dst, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  gather_rows_kernel<<<M, 256, 0, s>>>((const bf16*)src, ld_src, n_src_rows, idx, d, (bf16*)dst, ld_dst);
+  return hipGetLastError();
+}
+
+__global__ void to_bf16_kernel(const void* __restrict__ src, int src_is_f32, int64_t n, bf16* __restrict__ dst) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src_is_f32 ? (bf16)((const float*)src)[i] : ((const bf16*)src)[i];
+}
+
+hipError_t launch_to_bf16(const void* src, int src_is_f32, int64_t n, void* dst, hipStream_t s) {
+  to_bf16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(src, src_is_f32, n, (bf16*)dst);
+  return hipGetLastError();
+}
+
+// out[m] = the lowest index among the largest of logits[m][0 .. n).  One workgroup per row; a
+// thread walks its columns in increasing order, so within a thread "strictly greater" keeps the
+// first maximum, and the cross-thread reduction breaks value ties towards the lower index.
+// NaNs never win a comparison; a row of NaNs gives 0.
+__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ logits, int64_t ld, int n,
+                                                          int32_t* __restrict__ out) {
+  __shared__ float s_val[256];
+  __shared__ int s_idx[256];
+  const float* row = logits + (int64_t)blockIdx.x * ld;
+  float best = -INFINITY;
+  int bi = 0x7fffffff;
+  for (int j = threadIdx.x; j < n; j += 256) {
+    const float v = row[j];
+    if (v > best || (bi == 0x7fffffff && v == best)) {
+      best = v;
+      bi = j;
+    }
+  }
+  s_val[threadIdx.x] = best;
+  s_idx[threadIdx.x] = bi;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      const float v = s_val[threadIdx.x + off];
+      const int i = s_idx[threadIdx.x + off];
+      if (v > s_val[threadIdx.x] || (v == s_val[threadIdx.x] && i < s_idx[threadIdx.x])) {
+        s_val[threadIdx.x] = v;
+        s_idx[threadIdx.x] = i;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = s_idx[0] == 0x7fffffff ? 0 : s_idx[0];
+}
+
+hipError_t launch_argmax_rows(const float* logits, int64_t ld, int M, int n, int32_t* out, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  argmax_rows_kernel<<<M, 256, 0, s>>>(logits, ld, n, out);
+  return hipGetLastError();
+}
+
 }  // namespace tdp

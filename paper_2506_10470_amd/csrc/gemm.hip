@@ -746,7 +746,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.W = (const bf16*)a.W;
   p.out = (bf16*)a.out;
   p.residual = a.residual;
-  p.out_f32 = a.epilogue == EPI_RESIDUAL ? a.out_f32 : 0;
+  p.out_f32 = a.epilogue == EPI_SWIGLU ? 0 : a.out_f32;
   p.res_f32 = a.residual_f32;
   p.ws = a.workspace;
   p.a_lay = a.a_layout;

@@ -499,4 +499,146 @@ int tdp_stage_timing_read(tdp_stage* st, float* ms) {
   return TDP_OK;
 }
 
+// ---- the two ends of the pipeline ---------------------------------------------------------------
+
+struct tdp_ends {
+  tdp_ends_config cfg;
+  int64_t v_pad = 0;
+  uint16_t* table = nullptr;   // bf16 [vocab][d]
+  float* gain = nullptr;       // [d]
+  uint16_t* w_head = nullptr;  // bf16, pair-interleaved [v_pad][d]
+  uint16_t* rows = nullptr;    // bf16 [max_tokens][d]: gathered input rows
+  uint16_t* y = nullptr;       // bf16, pair-interleaved [max_tokens ^ 2][d]: normalised rows
+  float* logits = nullptr;     // [max_tokens][vocab]
+  float* ws = nullptr;
+  int64_t ws_elems = 0;
+};
+
+int tdp_ends_create(const tdp_ends_config* cfg, tdp_ends** out) {
+  if (!cfg || !out) return fail(TDP_EINVAL, "null pointer");
+  if (cfg->vocab_size < 4 || cfg->vocab_size % 4) return fail(TDP_EINVAL, "vocab_size must be a positive multiple of 4");
+  if (cfg->d_model < 64 || cfg->d_model % 64) return fail(TDP_EINVAL, "d_model must be a positive multiple of 64");
+  if (!(cfg->rms_eps >= 0.f)) return fail(TDP_EINVAL, "rms_eps must be >= 0");
+  if (cfg->max_tokens < 1) return fail(TDP_EINVAL, "max_tokens must be >= 1");
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) return fail(TDP_EHIP, "no HIP device");
+  tdp_ends* e = new (std::nothrow) tdp_ends();
+  if (!e) return fail(TDP_ENOMEM, "host allocation failed");
+  e->cfg = *cfg;
+  const int64_t d = cfg->d_model, V = cfg->vocab_size;
+  e->v_pad = round_up(V, 256);
+  const int64_t M = ((int64_t)cfg->max_tokens + 1) & ~1ll;
+  hipError_t err = gemm_setup();
+  auto A = [&](auto** p, int64_t n, bool zero) {
+    if (err == hipSuccess) err = dev_alloc(p, n, zero);
+  };
+  A(&e->table, V * d, true);
+  A(&e->gain, d, true);
+  A(&e->w_head, e->v_pad * d, true);
+  A(&e->rows, M * d, true);
+  A(&e->y, M * d, true);
+  A(&e->logits, (int64_t)cfg->max_tokens * V, false);
+  e->ws_elems = 2 * (M < 512 ? M : 512) * e->v_pad;
+  A(&e->ws, e->ws_elems, false);
+  if (err == hipSuccess) err = hipDeviceSynchronize();
+  if (err != hipSuccess) {
+    const int code = fail_hip(err, "tdp_ends_create");
+    tdp_ends_destroy(e);
+    return code;
+  }
+  *out = e;
+  return TDP_OK;
+}
+
+void tdp_ends_destroy(tdp_ends* e) {
+  if (!e) return;
+  (void)hipDeviceSynchronize();
+  void* ptrs[] = {e->table, e->gain, e->w_head, e->rows, e->y, e->logits, e->ws};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+  delete e;
+}
+
+int tdp_ends_set_weight(tdp_ends* e, int32_t which, const void* src, int32_t dtype, int32_t mem, int64_t rows,
+                        int64_t cols) {
+  if (!e || !src) return fail(TDP_EINVAL, "null ends object or source");
+  if (dtype != TDP_F32 && dtype != TDP_BF16) return fail(TDP_EINVAL, "dtype must be TDP_F32 or TDP_BF16");
+  if (mem != TDP_HOST && mem != TDP_DEVICE) return fail(TDP_EINVAL, "mem must be TDP_HOST or TDP_DEVICE");
+  const int64_t d = e->cfg.d_model, V = e->cfg.vocab_size;
+  int64_t er, ec;
+  switch (which) {
+    case TDP_E_EMBEDDING: er = V; ec = d; break;
+    case TDP_E_FINAL_NORM: er = d; ec = 1; break;
+    case TDP_E_LM_HEAD: er = d; ec = V; break;
+    default: return fail(TDP_EINVAL, "unknown weight id");
+  }
+  if (rows != er || cols != ec) return fail(TDP_EINVAL, "weight shape does not match the configuration");
+  const size_t esz = dtype == TDP_F32 ? 4 : 2;
+  const void* dsrc = src;
+  void* tmp = nullptr;
+  if (mem == TDP_HOST) {
+    HIP_TRY(hipMalloc(&tmp, (size_t)(rows * cols) * esz));
+    hipError_t err = hipMemcpy(tmp, src, (size_t)(rows * cols) * esz, hipMemcpyHostToDevice);
+    if (err != hipSuccess) {
+      (void)hipFree(tmp);
+      return fail_hip(err, "hipMemcpy(weight)");
+    }
+    dsrc = tmp;
+  }
+  const int f32 = dtype == TDP_F32;
+  hipError_t err;
+  if (which == TDP_E_EMBEDDING) err = launch_to_bf16(dsrc, f32, V * d, e->table, 0);
+  else if (which == TDP_E_FINAL_NORM) err = launch_convert_vec(dsrc, f32, d, e->gain, 0);
+  else err = launch_repack(dsrc, f32, d, V, e->w_head, d, 0, 0, 0);
+  if (err == hipSuccess) err = hipDeviceSynchronize();
+  if (tmp) (void)hipFree(tmp);
+  if (err != hipSuccess) return fail_hip(err, "weight conversion");
+  return TDP_OK;
+}
+
+int tdp_embed_tokens(tdp_ends* e, const int32_t* token_ids, int32_t M, void* hidden_out, void* stream) {
+  if (!e) return fail(TDP_EINVAL, "null ends object");
+  if (M < 0) return fail(TDP_EINVAL, "negative size");
+  if (M == 0) return TDP_OK;
+  if (!token_ids || !hidden_out) return fail(TDP_EINVAL, "null pointer");
+  HIP_TRY(launch_gather_rows(e->table, e->cfg.d_model, e->cfg.vocab_size, token_ids, M, e->cfg.d_model, hidden_out,
+                             e->cfg.d_model, (hipStream_t)stream));
+  return TDP_OK;
+}
+
+int tdp_lm_head(tdp_ends* e, const void* hidden_in, int32_t n_rows_in, const int32_t* row_index, int32_t M,
+                float* logits_out, int32_t* next_token, void* stream) {
+  if (!e) return fail(TDP_EINVAL, "null ends object");
+  if (M < 0 || n_rows_in < 0) return fail(TDP_EINVAL, "negative size");
+  if (M > e->cfg.max_tokens) return fail(TDP_EINVAL, "M exceeds max_tokens");
+  if (M == 0) return TDP_OK;
+  if (!hidden_in || n_rows_in < 1) return fail(TDP_EINVAL, "no input rows");
+  if (!row_index && M > n_rows_in) return fail(TDP_EINVAL, "M exceeds the input rows");
+  hipStream_t s = (hipStream_t)stream;
+  const int d = e->cfg.d_model, V = e->cfg.vocab_size;
+  const void* x = hidden_in;
+  if (row_index) {
+    HIP_TRY(launch_gather_rows(hidden_in, d, n_rows_in, row_index, M, d, e->rows, d, s));
+    x = e->rows;
+  }
+  HIP_TRY(launch_rmsnorm(x, 0, d, e->gain, e->cfg.rms_eps, M, d, e->y, layout_paired(d), s));
+  float* logits = logits_out ? logits_out : e->logits;
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.A = e->y; g.a_layout = layout_paired(d); g.W = e->w_head; g.Kpad = d; g.Npad = e->v_pad; g.M = M; g.N_store = V;
+  g.out = logits; g.ldo = V; g.epilogue = EPI_STORE; g.out_f32 = 1;
+  g.workspace = e->ws; g.workspace_elems = e->ws_elems;
+  HIP_TRY(launch_gemm(g, s));
+  if (next_token) HIP_TRY(launch_argmax_rows(logits, V, M, V, next_token, s));
+  return TDP_OK;
+}
+
+int tdp_argmax_rows(const float* logits, int32_t M, int32_t n, int64_t ld, int32_t* out, void* stream) {
+  if (M < 0 || n < 1 || ld < n) return fail(TDP_EINVAL, "bad shape");
+  if (M == 0) return TDP_OK;
+  if (!logits || !out) return fail(TDP_EINVAL, "null pointer");
+  HIP_TRY(launch_argmax_rows(logits, ld, M, n, out, (hipStream_t)stream));
+  return TDP_OK;
+}
+
 }  // extern "C"

@@ -41,7 +41,7 @@ struct GemmArgs {
   const void* residual;  // [M][ldr] or null, bf16 unless residual_f32
   int64_t ldr;
   int epilogue;
-  int out_f32;        // EPI_RESIDUAL only: the residual stream is kept in fp32 inside a stage
+  int out_f32;        // plain and residual epilogues: `out` is fp32 (residual stream inside a stage; logits)
   int residual_f32;
   float* workspace;       // fp32 split-K partials
   int64_t workspace_elems;
@@ -57,6 +57,14 @@ hipError_t gemm_setup();  // one-time function attributes (dynamic LDS size)
 hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in /*K*/, int64_t cols_out /*N*/,
                          void* dst, int64_t dst_ld, int64_t row_off, int mode, hipStream_t s);
 hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float* dst, hipStream_t s);
+
+// ---- pipeline ends ----------------------------------------------------------------------------
+// dst[m][:] = src[idx[m]][:] (bf16 rows of d elements, d a multiple of 8; indices clamped into range)
+hipError_t launch_gather_rows(const void* src, int64_t ld_src, int64_t n_src_rows, const int32_t* idx, int M, int d,
+                              void* dst, int64_t ld_dst, hipStream_t s);
+hipError_t launch_to_bf16(const void* src, int src_is_f32, int64_t n, void* dst, hipStream_t s);
+// out[m] = lowest index among the maxima of logits[m][0..n)
+hipError_t launch_argmax_rows(const float* logits, int64_t ld, int M, int n, int32_t* out, hipStream_t s);
 
 // ---- RMSNorm ---------------------------------------------------------------------------------
 hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float* gain, float eps, int M, int d,

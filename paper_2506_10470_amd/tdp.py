@@ -28,6 +28,14 @@ class StageConfig(C.Structure):
                 ("max_seqs", C.c_int32), ("max_pages_per_seq", C.c_int32)]
 
 
+class EndsConfig(C.Structure):
+    _fields_ = [("vocab_size", C.c_int32), ("d_model", C.c_int32), ("rms_eps", C.c_float),
+                ("max_tokens", C.c_int32)]
+
+
+E_EMBEDDING, E_FINAL_NORM, E_LM_HEAD = 0, 1, 2
+
+
 class TdpError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__("tdp error %d: %s" % (code, msg))
@@ -59,6 +67,12 @@ _SIGS = {
     "tdp_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "tdp_stage_timing_enable": (C.c_int, [_vp, _i32]),
     "tdp_stage_timing_read": (C.c_int, [_vp, C.POINTER(C.c_float)]),
+    "tdp_ends_create": (C.c_int, [C.POINTER(EndsConfig), C.POINTER(_vp)]),
+    "tdp_ends_destroy": (None, [_vp]),
+    "tdp_ends_set_weight": (C.c_int, [_vp, _i32, _vp, _i32, _i32, _i64, _i64]),
+    "tdp_embed_tokens": (C.c_int, [_vp, _vp, _i32, _vp, _vp]),
+    "tdp_lm_head": (C.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _vp]),
+    "tdp_argmax_rows": (C.c_int, [_vp, _i32, _i32, _i64, _vp, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -156,3 +170,30 @@ def tdp_stage_timing_read(st) -> dict:
     ms = (C.c_float * len(TIMING_CLASSES))()
     _check(lib.tdp_stage_timing_read(st, ms))
     return dict(zip(TIMING_CLASSES, [float(x) for x in ms]))
+
+
+def tdp_ends_create(cfg: EndsConfig) -> int:
+    h = _vp()
+    _check(lib.tdp_ends_create(C.byref(cfg), C.byref(h)))
+    return h.value
+
+
+def tdp_ends_destroy(e: int) -> None:
+    lib.tdp_ends_destroy(e)
+
+
+def tdp_ends_set_weight(e, which, src, dtype, mem, rows, cols) -> None:
+    _check(lib.tdp_ends_set_weight(e, which, _ptr(src), dtype, mem, rows, cols))
+
+
+def tdp_embed_tokens(e, token_ids, M, hidden_out, stream=None) -> None:
+    _check(lib.tdp_embed_tokens(e, _ptr(token_ids), M, _ptr(hidden_out), _stream(stream)))
+
+
+def tdp_lm_head(e, hidden_in, n_rows_in, row_index, M, logits_out, next_token, stream=None) -> None:
+    _check(lib.tdp_lm_head(e, _ptr(hidden_in), n_rows_in, _ptr(row_index), M, _ptr(logits_out), _ptr(next_token),
+                           _stream(stream)))
+
+
+def tdp_argmax_rows(logits, M, n, ld, out, stream=None) -> None:
+    _check(lib.tdp_argmax_rows(_ptr(logits), M, n, ld, _ptr(out), _stream(stream)))

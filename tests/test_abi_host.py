@@ -69,3 +69,22 @@ def test_layer_range_and_timing_calls_reject_null_stage():
     assert tdp.lib.tdp_stage_timing_enable(None, 1) == tdp.EINVAL
     assert tdp.lib.tdp_stage_kv_import(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL
     assert tdp.lib.tdp_stage_kv_export(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL
+
+
+def test_ends_entry_points_reject_bad_arguments():
+    import ctypes as C
+    for bad in [dict(vocab_size=0), dict(vocab_size=1001), dict(d_model=100), dict(rms_eps=-1.0), dict(max_tokens=0)]:
+        base = dict(vocab_size=1000, d_model=256, rms_eps=1e-5, max_tokens=8)
+        base.update(bad)
+        with pytest.raises(tdp.TdpError) as e:
+            tdp.tdp_ends_create(tdp.EndsConfig(**base))
+        assert e.value.code == tdp.EINVAL
+    assert tdp.lib.tdp_ends_create(None, None) == tdp.EINVAL
+    assert tdp.lib.tdp_embed_tokens(None, None, 1, None, None) == tdp.EINVAL
+    assert tdp.lib.tdp_lm_head(None, None, 1, None, 1, None, None, None) == tdp.EINVAL
+    assert tdp.lib.tdp_ends_set_weight(None, 0, None, 0, 0, 1, 1) == tdp.EINVAL
+    assert tdp.lib.tdp_argmax_rows(None, 1, 0, 0, None, None) == tdp.EINVAL
+    assert tdp.lib.tdp_argmax_rows(None, 1, 8, 4, None, None) == tdp.EINVAL      # ld < n
+    assert tdp.lib.tdp_argmax_rows(None, 1, 8, 8, None, None) == tdp.EINVAL      # null pointers
+    assert tdp.lib.tdp_argmax_rows(None, 0, 8, 8, None, None) == tdp.OK          # empty is a no-op
+    tdp.lib.tdp_ends_destroy(None)
