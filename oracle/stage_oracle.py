@@ -14,7 +14,9 @@ with grouped-query attention share each K/V head among several query heads
 (Sec. 4.1).  The paper takes the Llama-2 layer itself as given (Table 2); the
 layer below is that public definition: pre-norm residual blocks, RMSNorm,
 rotary position embedding in the half-split pairing, softmax attention with
-scale 1/sqrt(head_dim), SwiGLU feed-forward, no biases.
+scale 1/sqrt(head_dim), SwiGLU feed-forward, no biases.  The paper's third
+model (Qwen2.5-32B, Table 2) is the same layer with biases on the q / k / v
+projections; LayerWeights carries them as optional fields.
 
 Requests are independent, so the oracle works on ONE request at a time with a
 contiguous (unpaged) KV list: paging is the thing under test, not part of the
@@ -48,6 +50,12 @@ class LayerWeights:
     wd: np.ndarray
     g_attn: np.ndarray
     g_mlp: np.ndarray
+    # Optional biases of the q / k / v projections ([d_q], [d_kv], [d_kv]): the Qwen2.5 row of the
+    # paper's Table 2 is a Llama-style layer with exactly this addition (public model definition);
+    # None = no bias (Llama).
+    bq: Optional[np.ndarray] = None
+    bk: Optional[np.ndarray] = None
+    bv: Optional[np.ndarray] = None
 
 
 @dataclass
@@ -127,9 +135,16 @@ def layer_forward(x: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, w: La
     p0 = k_cache.shape[0]
     pos = np.arange(p0, p0 + L)
     y = rmsnorm(x, w.g_attn, sh.rms_eps)
-    q = (y @ w.wq).reshape(L, sh.n_q_heads, sh.head_dim)
-    k = (y @ w.wk).reshape(L, sh.n_kv_heads, sh.head_dim)
-    v = (y @ w.wv).reshape(L, sh.n_kv_heads, sh.head_dim)
+    q, k, v = y @ w.wq, y @ w.wk, y @ w.wv
+    if w.bq is not None:
+        q = q + np.asarray(w.bq, F64)  # the bias joins the projection before the rotation
+    if w.bk is not None:
+        k = k + np.asarray(w.bk, F64)
+    if w.bv is not None:
+        v = v + np.asarray(w.bv, F64)
+    q = q.reshape(L, sh.n_q_heads, sh.head_dim)
+    k = k.reshape(L, sh.n_kv_heads, sh.head_dim)
+    v = v.reshape(L, sh.n_kv_heads, sh.head_dim)
     q = rope(q, pos, sh.rope_base)
     k = rope(k, pos, sh.rope_base)
     k_all = np.concatenate([np.asarray(k_cache, F64), k], axis=0)

@@ -358,3 +358,75 @@ def test_final_logits_closed_forms():
     assert np.allclose(E.final_logits(x, g, w, 1e-5), E.final_logits(x, ones, g[:, None] * w, 1e-5))
     # a dropped norm would fail this: logits of a huge input stay bounded
     assert np.max(np.abs(E.final_logits(1e6 * x, ones, w, 1e-5))) < 1e3
+
+
+# ---------------------------------------------------------------- q / k / v biases (Qwen-style layer)
+
+def _with_bias(w, bq, bk, bv):
+    import dataclasses
+    return dataclasses.replace(w, bq=bq, bk=bk, bv=bv)
+
+
+def test_zero_bias_is_no_bias():
+    w = rand_layer(D, 4, 2, 8, F)
+    x = RNG.normal(size=(5, D))
+    e = O.empty_cache(SH)
+    a = O.layer_forward(x, e, e, w, SH)
+    b = O.layer_forward(x, e, e, _with_bias(w, np.zeros(32), np.zeros(16), np.zeros(16)), SH)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_bias_equals_an_extra_weight_row_fed_by_a_constant_channel():
+    """q = y W + b is the product of [y, c] with [[W], [b / c]]: build a layer of width D+1 whose
+    last normalised channel is a known constant and whose extra weight rows carry the biases."""
+    rng = np.random.default_rng(41)
+    w = rand_layer(D, 4, 2, 8, F, rng=rng)
+    bq, bk, bv = rng.normal(size=32), rng.normal(size=16), rng.normal(size=16)
+    x = rng.normal(size=(6, D))
+    e = O.empty_cache(SH)
+    want = O.layer_forward(x, e, e, _with_bias(w, bq, bk, bv), SH)
+    # reference composed by hand from the oracle's own building blocks, bias as an augmented product
+    y = O.rmsnorm(x, w.g_attn, SH.rms_eps)
+    ya = np.concatenate([y, np.ones((6, 1))], axis=1)
+    q = (ya @ np.vstack([w.wq, bq])).reshape(6, 4, 8)
+    k = (ya @ np.vstack([w.wk, bk])).reshape(6, 2, 8)
+    v = (ya @ np.vstack([w.wv, bv])).reshape(6, 2, 8)
+    pos = np.arange(6)
+    q, k = O.rope(q, pos, SH.rope_base), O.rope(k, pos, SH.rope_base)
+    a = O.attention(q, k, v, 0, SH)
+    h = x + a @ w.wo
+    y2 = O.rmsnorm(h, w.g_mlp, SH.rms_eps)
+    out = h + (O.silu(y2 @ w.wg) * (y2 @ w.wu)) @ w.wd
+    assert np.allclose(want[0], out, rtol=1e-12, atol=1e-12)
+    assert np.allclose(want[1], k) and np.allclose(want[2], v)
+
+
+def test_value_bias_shifts_the_attention_output_by_itself():
+    """Softmax weights sum to 1, so adding b_v to every value adds b_v (per head) to the attention
+    output and b_v-through-W_o to the residual branch - whatever q and k are."""
+    rng = np.random.default_rng(42)
+    w = rand_layer(D, 4, 2, 8, F, rng=rng)
+    # kill the MLP branch so the layer output is x + attn @ wo
+    w.wd[:] = 0.0
+    bv = rng.normal(size=16)
+    x = rng.normal(size=(5, D))
+    e = O.empty_cache(SH)
+    plain = O.layer_forward(x, e, e, w, SH)[0]
+    shifted = O.layer_forward(x, e, e, _with_bias(w, None, None, bv), SH)[0]
+    per_q_head = np.repeat(bv.reshape(2, 8), 2, axis=0).reshape(-1)      # kv head h serves q heads 2h, 2h+1
+    assert np.allclose(shifted - plain, np.tile(per_q_head @ w.wo, (5, 1)), atol=1e-12)
+
+
+def test_key_bias_is_rotated_with_the_key():
+    """The cached key is rope(y W_k + b_k): with W_k = 0 the cache holds the rotated bias alone."""
+    rng = np.random.default_rng(43)
+    w = rand_layer(D, 4, 2, 8, F, rng=rng)
+    w.wk[:] = 0.0
+    bk = rng.normal(size=16)
+    x = rng.normal(size=(4, D))
+    e = O.empty_cache(SH)
+    _, k_all, _ = O.layer_forward(x, e, e, _with_bias(w, None, bk, None), SH)
+    want = O.rope(np.tile(bk.reshape(1, 2, 8), (4, 1, 1)), np.arange(4), SH.rope_base)
+    assert np.allclose(k_all, want, atol=1e-14)
+    assert not np.allclose(k_all[1], bk.reshape(2, 8))                   # position 1 really is rotated
