@@ -245,7 +245,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="70b_quarter", choices=["70b_quarter", "13b_quarter", "7b_quarter"])
+    ap.add_argument("--workload", default="70b_quarter", choices=["70b_quarter", "13b_quarter", "7b_quarter", "qwen32b_quarter"])
     ap.add_argument("--batch", type=int, default=512)
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only)")
     ap.add_argument("--no-sweep", action="store_true")
@@ -272,7 +272,7 @@ def main():
     if args.layers:
         shape = shape.with_layers(args.layers)
     B = args.batch
-    n_prompts = {"70b_quarter": 16, "13b_quarter": 32, "7b_quarter": 32}[args.workload]
+    n_prompts = {"70b_quarter": 16, "13b_quarter": 32, "7b_quarter": 32, "qwen32b_quarter": 32}[args.workload]
     dec_ctx = W.decode_ctx_lens(args.workload, B)
     pre_lens = W.prefill_seq_lens(args.workload, n_prompts)
     st, dec, pre, pre_tables, cu = build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32)

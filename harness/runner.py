@@ -39,7 +39,7 @@ class Stage:
     def load_weights(self, dtype=torch.bfloat16):
         tdp, sh = self.tdp, self.shape
         for l in range(sh.n_layers):
-            for name in W.WEIGHT_NAMES:
+            for name in W.WEIGHT_NAMES + (W.BIAS_NAMES if sh.qkv_bias else ()):
                 w = W.weight(sh, l, name, device="cuda", dtype=dtype).contiguous()
                 rows = w.shape[0]
                 cols = w.shape[1] if w.dim() == 2 else 1

@@ -131,6 +131,7 @@ class StageShape:
     rope_base: float = 10000.0
     page_size: int = PAGE_SIZE
     config_index: int = 0
+    qkv_bias: bool = False
 
     @property
     def group(self) -> int:
@@ -155,9 +156,16 @@ SHAPES: Dict[str, StageShape] = {
     "7b_quarter": StageShape("7b_quarter", 8, 4096, 32, 32, 128, 11008, config_index=1),
     "13b_quarter": StageShape("13b_quarter", 10, 5120, 40, 40, 128, 13824, config_index=2),
     "70b_quarter": StageShape("70b_quarter", 20, 8192, 64, 8, 128, 28672, config_index=4),
+    # Qwen2.5-32B-shaped (paper Table 2: 64 layers, hidden 5120, 40 heads; public model: 8 KV heads,
+    # FFN 27648, q/k/v biases, eps 1e-6, rope base 1e6): a quarter is 16 layers
+    "qwen32b_quarter": StageShape("qwen32b_quarter", 16, 5120, 40, 8, 128, 27648, rms_eps=1e-6,
+                                  rope_base=1000000.0, config_index=5, qkv_bias=True),
+    "tiny_bias": StageShape("tiny_bias", 2, 320, 10, 2, 64, 688, rms_eps=1e-6, rope_base=1000000.0,
+                            config_index=0, qkv_bias=True),
 }
 
 WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g_attn", "g_mlp")
+BIAS_NAMES = ("bq", "bk", "bv")   # only for shapes with qkv_bias
 
 
 def weight_shape(sh: StageShape, which: str) -> Tuple[int, ...]:
@@ -166,6 +174,7 @@ def weight_shape(sh: StageShape, which: str) -> Tuple[int, ...]:
         "wq": (sh.d_model, sh.d_q), "wk": (sh.d_model, sh.d_kv), "wv": (sh.d_model, sh.d_kv),
         "wo": (sh.d_q, sh.d_model), "wg": (sh.d_model, sh.d_ff), "wu": (sh.d_model, sh.d_ff),
         "wd": (sh.d_ff, sh.d_model), "g_attn": (sh.d_model,), "g_mlp": (sh.d_model,),
+        "bq": (sh.d_q,), "bk": (sh.d_kv,), "bv": (sh.d_kv,),
     }[which]
 
 
@@ -173,8 +182,11 @@ def weight(sh: StageShape, layer: int, which: str, device="cpu", dtype=torch.bfl
            seed: int = BASE_SEED) -> torch.Tensor:
     """Matrices ~ N(0, 0.02); norm gains ~ 1 + N(0, 0.02) (a gain of exactly 1
     would hide a dropped-gain bug)."""
-    key = stream_key(seed, 1000 * sh.config_index, 1, layer, WEIGHT_NAMES.index(which))
     shape = weight_shape(sh, which)
+    if which in BIAS_NAMES:  # ~ N(0, 0.5): large enough that a dropped or misplaced bias is far outside tolerance
+        key = stream_key(seed, 1000 * sh.config_index, 6, layer, BIAS_NAMES.index(which))
+        return normal_tensor(key, shape, 0.5, 0.0, device, dtype)
+    key = stream_key(seed, 1000 * sh.config_index, 1, layer, WEIGHT_NAMES.index(which))
     mean = 1.0 if which.startswith("g_") else 0.0
     return normal_tensor(key, shape, 0.02, mean, device, dtype)
 
@@ -294,7 +306,7 @@ def decode_ctx_lens(config: str, batch: int, seed: int = BASE_SEED) -> np.ndarra
     if config == "7b_quarter":      # prompt LN(256, .8) in [16,2048] + generated U[0,512]
         return lognormal_lengths(stream_key(k, 1), batch, 256, 0.8, 16, 2048) + \
             uniform_lengths(stream_key(k, 2), batch, 0, 512)
-    if config == "13b_quarter":     # prompt LN(384, .7) + generated U[0,1024], clipped to 4096
+    if config in ("13b_quarter", "qwen32b_quarter"):  # prompt LN(384, .7) + generated U[0,1024], clipped to 4096
         p = lognormal_lengths(stream_key(k, 1), batch, 384, 0.7, 16, 4096)
         return np.minimum(p + uniform_lengths(stream_key(k, 2), batch, 0, 1024), 4096)
     if config == "70b_quarter":     # LN(1024, .6) in [64,4096]
@@ -308,7 +320,7 @@ def prefill_seq_lens(config: str, n_seqs: int, seed: int = BASE_SEED) -> np.ndar
         return uniform_lengths(k, n_seqs, 8, 32)
     if config == "7b_quarter":
         return lognormal_lengths(k, n_seqs, 256, 0.8, 16, 2048)
-    if config == "13b_quarter":
+    if config in ("13b_quarter", "qwen32b_quarter"):
         return lognormal_lengths(k, n_seqs, 384, 0.7, 16, 4096)
     if config == "70b_quarter":
         return lognormal_lengths(k, n_seqs, 1024, 0.6, 64, 4096)

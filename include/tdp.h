@@ -49,6 +49,11 @@ extern "C" {
 #define TDP_WD      6      /* [d_ff, d_model]   down         */
 #define TDP_G_ATTN  7      /* [d_model] RMSNorm gain before attention */
 #define TDP_G_MLP   8      /* [d_model] RMSNorm gain before the MLP   */
+/* optional biases of the q / k / v projections (the Qwen2.5-32B model of the paper's Table 2 has
+ * them; a stage whose biases are never set runs without): vectors [d_q, 1], [d_kv, 1], [d_kv, 1] */
+#define TDP_BQ 9
+#define TDP_BK 10
+#define TDP_BV 11
 
 #define TDP_F32     0
 #define TDP_BF16    1

@@ -26,6 +26,7 @@ struct GemmParams {
   const bf16* W;
   bf16* out;
   const void* residual;  // bf16, or fp32 when res_f32
+  const float* bias;     // fp32 [Npad] or null
   float* ws;
   OperandLayout a_lay, w_lay, u_lay;
   int64_t Kpad, Npad, ldo, ldr;
@@ -39,6 +40,11 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 
 // Residual add and store of four consecutive output columns (plain / residual epilogues).
 __device__ __forceinline__ void store_row4(const GemmParams& p, int m, int n, float (&v)[4]) {
+  if (p.bias) {
+    const f32x4 b = *reinterpret_cast<const f32x4*>(p.bias + n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += b[e];
+  }
   if (p.epilogue == EPI_RESIDUAL) {
     if (p.res_f32) {
       const f32x4 r = *reinterpret_cast<const f32x4*>((const float*)p.residual + (int64_t)m * p.ldr + n);
@@ -746,6 +752,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.W = (const bf16*)a.W;
   p.out = (bf16*)a.out;
   p.residual = a.residual;
+  p.bias = a.epilogue == EPI_SWIGLU ? nullptr : a.bias;
   p.out_f32 = a.epilogue == EPI_SWIGLU ? 0 : a.out_f32;
   p.res_f32 = a.residual_f32;
   p.ws = a.workspace;

@@ -41,6 +41,8 @@ struct tdp_stage {
   int64_t dq, Nqkv, Nqkv_pad, d_pad, Fpad, Ngu_pad;
   uint16_t *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wd = nullptr;  // bf16 bits
   float *g_attn = nullptr, *g_mlp = nullptr;
+  float* bqkv = nullptr;  // [L][Nqkv_pad]: q / k / v projection biases, zero until set
+  bool has_bias = false;
   uint16_t *kpool = nullptr, *vpool = nullptr;
   int64_t pool_elems = 0;  // per layer, per pool
   uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *u = nullptr;  // bf16 activations
@@ -163,7 +165,9 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
       g.W = st->wqkv + (int64_t)l * st->Nqkv_pad * d; g.Kpad = d; g.Npad = st->Nqkv_pad;
       g.N_store = (int)st->Nqkv_pad; g.out = st->qkv; g.ldo = st->Nqkv_pad;
       g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE; g.out_f32 = 0; g.residual_f32 = 0;
+      g.bias = st->has_bias ? st->bqkv + (int64_t)l * st->Nqkv_pad : nullptr;
       HIP_TRY(launch_gemm(g, s));
+      g.bias = nullptr;
     }
     {  // a3: rotary embedding + KV append
       Timer t(st, s, T_ROPE);
@@ -252,6 +256,7 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
   A(&st->wd, L * st->d_pad * st->Fpad, true);
   A(&st->g_attn, L * d, true);
   A(&st->g_mlp, L * d, true);
+  A(&st->bqkv, L * st->Nqkv_pad, true);
   A(&st->kpool, L * st->pool_elems, true);
   A(&st->vpool, L * st->pool_elems, true);
   const int64_t M = (st->maxM + 1) & ~1;  // row pairs: pair-interleaved activation buffers
@@ -299,7 +304,7 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
 void tdp_stage_destroy(tdp_stage* st) {
   if (!st) return;
   (void)hipDeviceSynchronize();
-  void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->kpool, st->vpool, st->y,
+  void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->bqkv, st->kpool, st->vpool, st->y,
                   st->qkv, st->attn, st->h, st->u, st->xa, st->xb, st->ws, st->part_o, st->part_ml,
                   st->attn_items, st->attn_n_items, st->rope_table};
   for (void* p : ptrs)
@@ -325,6 +330,8 @@ int tdp_stage_set_weight(tdp_stage* st, int32_t layer, int32_t which, const void
     case TDP_WG: case TDP_WU: er = d; ec = F; break;
     case TDP_WD: er = F; ec = d; break;
     case TDP_G_ATTN: case TDP_G_MLP: er = d; ec = 1; break;
+    case TDP_BQ: er = st->dq; ec = 1; break;
+    case TDP_BK: case TDP_BV: er = dkv; ec = 1; break;
     default: return fail(TDP_EINVAL, "unknown weight id");
   }
   if (rows != er || cols != ec) {
@@ -364,6 +371,15 @@ int tdp_stage_set_weight(tdp_stage* st, int32_t layer, int32_t which, const void
       e = launch_repack(dsrc, f32, rows, cols, st->wd + (int64_t)layer * st->d_pad * st->Fpad, st->Fpad, 0, 0, 0); break;
     case TDP_G_ATTN:
       e = launch_convert_vec(dsrc, f32, d, st->g_attn + (int64_t)layer * d, 0); break;
+    case TDP_BQ:
+      e = launch_convert_vec(dsrc, f32, st->dq, st->bqkv + (int64_t)layer * st->Nqkv_pad, 0);
+      st->has_bias = true; break;
+    case TDP_BK:
+      e = launch_convert_vec(dsrc, f32, dkv, st->bqkv + (int64_t)layer * st->Nqkv_pad + st->dq, 0);
+      st->has_bias = true; break;
+    case TDP_BV:
+      e = launch_convert_vec(dsrc, f32, dkv, st->bqkv + (int64_t)layer * st->Nqkv_pad + st->dq + dkv, 0);
+      st->has_bias = true; break;
     default:
       e = launch_convert_vec(dsrc, f32, d, st->g_mlp + (int64_t)layer * d, 0); break;
   }

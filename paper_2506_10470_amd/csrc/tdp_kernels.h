@@ -38,6 +38,7 @@ struct GemmArgs {
   void* out;          // [M][ldo], bf16 unless out_f32; EPI_SWIGLU: bf16 in u_layout instead
   int64_t ldo;
   OperandLayout u_layout;
+  const float* bias;     // [Npad] fp32 or null: added to every row (plain / residual epilogues)
   const void* residual;  // [M][ldr] or null, bf16 unless residual_f32
   int64_t ldr;
   int epilogue;

@@ -12,9 +12,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TDP_LIB", os.path.join(_HERE, "libtdp.so"))   # TDP_LIB: alternative build
 
 OK, EINVAL, ENOMEM, EHIP = 0, -1, -2, -3
-WQ, WK, WV, WO, WG, WU, WD, G_ATTN, G_MLP = range(9)
+WQ, WK, WV, WO, WG, WU, WD, G_ATTN, G_MLP, BQ, BK, BV = range(12)
 WEIGHT_IDS = {"wq": WQ, "wk": WK, "wv": WV, "wo": WO, "wg": WG, "wu": WU, "wd": WD,
-              "g_attn": G_ATTN, "g_mlp": G_MLP}
+              "g_attn": G_ATTN, "g_mlp": G_MLP, "bq": BQ, "bk": BK, "bv": BV}
 F32, BF16 = 0, 1
 HOST, DEVICE = 0, 1
 TIMING_CLASSES = ("rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gate_up", "gemm_down")

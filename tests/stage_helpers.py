@@ -26,10 +26,11 @@ def oracle_layer(sh: W.StageShape, layer: int, dtype=torch.bfloat16, device=None
     device = device or _gen_device()
     def get(name):
         w = W.weight(sh, layer, name, device=device, dtype=dtype)
-        if not name.startswith("g_"):
-            w = w.to(torch.bfloat16)      # matrices are held in bf16 by the stage; gains stay fp32
+        if not name.startswith(("g_", "b")):
+            w = w.to(torch.bfloat16)      # matrices are held in bf16 by the stage; gains and biases stay fp32
         return w.to("cpu").to(torch.float64).numpy()
-    return O.LayerWeights(*(get(n) for n in W.WEIGHT_NAMES))
+    biases = {n: get(n) for n in W.BIAS_NAMES} if sh.qkv_bias else {}
+    return O.LayerWeights(*(get(n) for n in W.WEIGHT_NAMES), **biases)
 
 
 def oracle_layers(sh: W.StageShape, dtype=torch.bfloat16, device=None):
@@ -68,9 +69,10 @@ def layer_forward_bf16_operands(x, k_cache, v_cache, w: O.LayerWeights, sh: O.Sh
     L, p0 = x.shape[0], k_cache.shape[0]
     pos = np.arange(p0, p0 + L)
     y = rb(O.rmsnorm(x, w.g_attn, sh.rms_eps))
-    q = rb(O.rope(rb(y @ w.wq).reshape(L, sh.n_q_heads, sh.head_dim), pos, sh.rope_base))
-    k = rb(O.rope(rb(y @ w.wk).reshape(L, sh.n_kv_heads, sh.head_dim), pos, sh.rope_base))
-    v = rb(y @ w.wv).reshape(L, sh.n_kv_heads, sh.head_dim)
+    bias = lambda b: 0.0 if b is None else np.asarray(b, np.float64)
+    q = rb(O.rope(rb(y @ w.wq + bias(w.bq)).reshape(L, sh.n_q_heads, sh.head_dim), pos, sh.rope_base))
+    k = rb(O.rope(rb(y @ w.wk + bias(w.bk)).reshape(L, sh.n_kv_heads, sh.head_dim), pos, sh.rope_base))
+    v = rb(y @ w.wv + bias(w.bv)).reshape(L, sh.n_kv_heads, sh.head_dim)
     k_all = np.concatenate([np.asarray(k_cache, np.float64), k], axis=0)
     v_all = np.concatenate([np.asarray(v_cache, np.float64), v], axis=0)
     a = rb(O.attention(q, k_all, v_all, p0, sh))

@@ -203,12 +203,12 @@ def test_prefill_tiny_config(tdp):
     run_prefill_case(tdp, "tiny", W.prefill_seq_lens("tiny", 4))
 
 
-@pytest.mark.parametrize("shape", ["tiny", "tiny_gqa", "tiny_h128"])
+@pytest.mark.parametrize("shape", ["tiny", "tiny_gqa", "tiny_h128", "tiny_bias"])
 def test_prefill_then_decode_across_page_boundaries(tdp, shape):
     run_prefill_case(tdp, shape, [1, 15, 16, 17, 33, 70], decode_steps=3)
 
 
-@pytest.mark.parametrize("shape", ["tiny_gqa", "tiny_h128"])
+@pytest.mark.parametrize("shape", ["tiny_gqa", "tiny_h128", "tiny_bias"])
 def test_decode_edge_contexts(tdp, shape):
     """ctx = 0 (attention over the token itself), page edges, split edges (256 tokens per split)."""
     run_decode_case(tdp, shape, [0, 1, 15, 16, 31, 32, 255, 256, 257, 511, 512, 700])
@@ -338,3 +338,25 @@ def test_decode_70b_shaped_layer_gqa(tdp):
     """One 70B-shaped layer (64 query heads on 8 KV heads), batch 24."""
     ctx = np.minimum(W.decode_ctx_lens("70b_quarter", 24), 700)
     run_decode_case(tdp, "70b_quarter", ctx, n_layers=1)
+
+
+def test_a_dropped_bias_would_be_caught(tdp):
+    """The biased stage must differ from the same stage without biases by far more than the
+    tolerance: otherwise the bias tests above would pass vacuously."""
+    from dataclasses import replace
+    sh = W.SHAPES["tiny_bias"]
+    ctx = np.array([5, 40], dtype=np.int32)
+    outs = []
+    for biased in (True, False):
+        db = W.make_decode_batch(ctx)
+        with Stage(tdp, replace(sh, qkv_bias=biased), db.num_pages, 2, 0, 0, db.tables.shape[1]) as st:
+            cu = np.array([0, 5, 45], dtype=np.int32)
+            k = W.kv_packed(sh, 0, "k", 45, 1, device="cuda")
+            for l in range(sh.n_layers):
+                tdp.tdp_stage_kv_import(st.h, l, k, k, i32(cu), i32(db.tables), 2, 45)
+            x = W.hidden_states(sh, 2, 1, device="cuda")
+            out = torch.empty_like(x)
+            tdp.tdp_stage_decode(st.h, x, i32(ctx), i32(db.tables), 2, out)
+            torch.cuda.synchronize()
+            outs.append(f64(out))
+    assert row_rel_err(outs[0], outs[1]) > 3 * TOL

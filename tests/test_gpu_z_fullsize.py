@@ -189,3 +189,8 @@ def test_70b_quarter_stage_decode_512_and_prefill_16_prompts(tdp):
     """Configuration 4 (the benchmark's headline): 20 layers, GQA 64/8 x 128, FFN 28672, decode
     batch 512 (and 256), 16-prompt prefill."""
     run_full_size(tdp, "70b_quarter", [256, 512], 16, n_prefill_samples=1)
+
+
+def test_qwen32b_quarter_stage_decode_256_and_prefill(tdp):
+    """The paper's third model (Table 2): GQA group of 5, q/k/v biases, rope base 1e6, eps 1e-6."""
+    run_full_size(tdp, "qwen32b_quarter", [256], 16, n_prefill_samples=1)
