@@ -373,7 +373,7 @@ def main():
         # prefill time against packed tokens (first k prompts): the profile the scheduler plans with
         curve = []
         for k in (1, 2, 4, 8):
-            if k >= len(pre_lens):
+            if k >= len(pre_lens) or args.no_sweep:
                 continue
             Tk = int(pre.cu_seqlens[k])
             msk = time_calls(lambda: tdp.tdp_stage_prefill(st.h, xp, cu_p, tab_p, k, Tk, op, stream), 1, 2)
