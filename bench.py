@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+ADVANCE_STEPS = 17             # the advancing-context run crosses a page boundary in every request
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 
@@ -35,8 +36,8 @@ def log(*a):
 def build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32):
     """One stage sized for the decode batch and the prefill batch, page ranges disjoint."""
     import torch
-    max_pps = 4096 // 16 + 1
-    dec = W.make_decode_batch(dec_ctx, max_pages_per_seq=max_pps)
+    max_pps = 4096 // 16 + 2
+    dec = W.make_decode_batch(dec_ctx, max_pages_per_seq=max_pps, steps=ADVANCE_STEPS + 1)
     pre = W.make_prefill_batch(pre_lens, max_pages_per_seq=max_pps)
     pre_tables = np.where(pre.tables >= 0, pre.tables + dec.num_pages, -1).astype(np.int32)
     t0 = time.time()
@@ -70,6 +71,20 @@ def time_calls(fn, warmup, steps):
         fn()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def step_percentiles(fn, steps):
+    """p10 / p50 / p90 of single-step times from events on the launch stream (torch's current stream)."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+    pick = lambda q: round(t[min(len(t) - 1, int(q * len(t)))], 4)
+    return {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90), "steps": steps}
 
 
 def class_times(tdp, st, fn, reps):
@@ -298,6 +313,16 @@ def main():
     work = A.decode_step_work(*sargs, dec_ctx)
     log("decode B=%d: %.3f ms/step, %.0f tok/s, %.0f GB/s algorithmic" % (B, ms, B / ms * 1e3,
                                                                           work["bytes"] / ms / 1e6))
+    pct = step_percentiles(decode_fn, max(args.steps, 20))
+    # the same step repeated rewrites the same KV slot; this run advances every context by one token
+    # per step instead, so each request crosses a page boundary once within ADVANCE_STEPS steps
+    ctx_run = ctx_d.clone()
+
+    def advancing_fn():
+        tdp.tdp_stage_decode(st.h, x, ctx_run, tab_d, B, out, stream)
+        ctx_run.add_(1)
+
+    ms_adv = time_calls(advancing_fn, 0, ADVANCE_STEPS)
     ct = class_times(tdp, st, decode_fn, 5)
     kern = kernel_rooflines(shape, B, work["kv_read_bytes"], work["attn_flops"], ct, "decode")
     workload_name = "%s stage, decode phase, batch %d" % (args.workload, B)
@@ -326,6 +351,7 @@ def main():
                    "hbm_gbs": round(work["bytes"] / ms / 1e6, 1),
                    "hbm_frac": round(work["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
                    "composite_t_min_ms": round(t_min, 3), "composite_frac": round(t_min / ms, 4),
+                   "step_ms_percentiles": pct, "advancing_context_ms_per_step": round(ms_adv, 4),
                    "class_ms": {k: round(v, 4) for k, v in ct.items()}, "kernels": kern},
     }
 

@@ -342,10 +342,10 @@ def serving_requests(n: int, seed: int = BASE_SEED) -> np.ndarray:
 
 
 def make_decode_batch(ctx_lens: np.ndarray, page_size: int = PAGE_SIZE, seed: int = BASE_SEED,
-                      max_pages_per_seq: int | None = None) -> DecodeBatch:
-    """Pages are reserved for ctx+1 tokens: the step appends one token."""
+                      max_pages_per_seq: int | None = None, steps: int = 1) -> DecodeBatch:
+    """Pages are reserved for ctx+steps tokens: every decode step appends one token."""
     ctx_lens = np.asarray(ctx_lens, dtype=np.int64)
-    tab, npg = block_tables(stream_key(seed, 12, len(ctx_lens)), ctx_lens + 1, page_size,
+    tab, npg = block_tables(stream_key(seed, 12, len(ctx_lens)), ctx_lens + steps, page_size,
                             max_pages_per_seq=max_pages_per_seq)
     return DecodeBatch(ctx_lens.astype(np.int32), tab, npg)
 
