@@ -29,13 +29,17 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf: exp2 gives exa
 // holds no workgroup that finds nothing to do except at its very end.
 // =====================================================================================
 
-// items[i] = (request, span index); n_items[0] = count.  One workgroup, any batch size.
+// items[i] = (request, span index, tokens to attend to = ctx + 1, 0) for i < n_items[0], and
+// (-1, ...) for the rest of the list up to max_items, so a workgroup learns everything about its
+// work - or that it has none - from one 16-byte record.  One workgroup, any batch size.
 // Longest work first: all full spans, then the requests' last (partial) spans by quarter of
 // span_len, longest quarter first, so the workgroups that run at the end of the launch are short.
 __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restrict__ ctx_lens, int batch, int span_len,
-                                                        int2* __restrict__ items, int32_t* __restrict__ n_items) {
+                                                        int4* __restrict__ items, int max_items,
+                                                        int32_t* __restrict__ n_items) {
   constexpr int NB = 5;  // class 0: full spans; 1..4: last span with > 3/4, > 1/2, > 1/4, > 0 of span_len
   __shared__ int part[NB][256];
+  __shared__ int s_total;
   const int tid = threadIdx.x;
   const int per = (batch + 255) / 256;
   const int b0 = tid * per, b1 = min(b0 + per, batch);
@@ -61,23 +65,39 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restric
         acc += v;
       }
     n_items[0] = acc;
+    s_total = acc;
   }
   __syncthreads();
   for (int b = b0; b < b1; ++b) {
     const int n_total = ctx_lens[b] + 1;
     const int n = (n_total + span_len - 1) / span_len;
-    for (int k = 0; k < n - 1; ++k) items[part[0][tid]++] = make_int2(b, k);  // part[c][tid]: this thread's cursor
-    items[part[last_class(n_total, n)][tid]++] = make_int2(b, n - 1);
+    for (int k = 0; k < n - 1; ++k) items[part[0][tid]++] = make_int4(b, k, n_total, 0);  // part[c][tid]: cursor
+    items[part[last_class(n_total, n)][tid]++] = make_int4(b, n - 1, n_total, 0);
+  }
+  for (int i = s_total + tid; i < max_items; i += 256) items[i] = make_int4(-1, 0, 0, 0);
+}
+
+// item_pages[i][j] = physical page of the j-th 16-token page of item i's span (span_len / 16
+// entries), entries past the request's last page clamped to it.  With this list a decode
+// workgroup needs no look-up that depends on another look-up before its first K/V load.
+__global__ __launch_bounds__(64) void attn_plan_pages_kernel(const int4* __restrict__ items,
+                                                             const int32_t* __restrict__ block_tables,
+                                                             int max_pages_per_seq, int pages_per_span,
+                                                             int32_t* __restrict__ item_pages) {
+  const int4 it = items[blockIdx.x];
+  if (it.x < 0) return;
+  const int last_page = (it.z - 1) / 16;
+  for (int j = threadIdx.x; j < pages_per_span; j += 64) {
+    const int p = min(it.y * pages_per_span + j, last_page);
+    item_pages[(int64_t)blockIdx.x * pages_per_span + j] = block_tables[(int64_t)it.x * max_pages_per_seq + p];
   }
 }
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
+__global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
                                                           int n_q_heads, KvLayout kv,
-                                                          const int32_t* __restrict__ ctx_lens,
-                                                          const int32_t* __restrict__ block_tables,
-                                                          int max_pages_per_seq, const int2* __restrict__ items,
-                                                          const int32_t* __restrict__ n_items,
+                                                          const int4* __restrict__ items,
+                                                          const int32_t* __restrict__ item_pages,
                                                           float* __restrict__ part_o, float* __restrict__ part_ml,
                                                           int max_spans, int span_len, bf16* __restrict__ out,
                                                           OperandLayout out_lay, float scale_log2) {
@@ -85,14 +105,21 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict
   constexpr int DT = DH / 16;   // 16-channel tiles of the output
   const int Hkv = kv.n_kv_heads;
   const int item = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
-  if (item >= n_items[0]) return;
-  const int2 it = items[item];
+  // the two look-ups a workgroup starts with are independent of each other: its work record and
+  // its span's page list (lane j holds pages j, 64 + j, ...; at most 256 pages per span)
+  const int pages_per_span = span_len >> 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int my_pages[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    my_pages[j] = item_pages[(int64_t)item * pages_per_span + min(lane + 64 * j, pages_per_span - 1)];
+  const int4 it = items[item];
+  if (it.x < 0) return;
   const int b = it.x, span = it.y;
-  const int n_total = ctx_lens[b] + 1;  // the new token's K/V were appended before this kernel
+  const int n_total = it.z;  // ctx + 1: the new token's K/V were appended before this kernel
   const int s_begin = span * span_len;
   const int s_end = min(s_begin + span_len, n_total);
   const int G = n_q_heads / Hkv;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, kg = lane >> 4;
   const bf16* kpool = (const bf16*)kv.k_pool;
   const bf16* vpool = (const bf16*)kv.v_pool;
@@ -113,15 +140,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict
   float m = kNegBig, lsum = 0.f;
 
   if (t_begin < t_end) {
-    const int32_t* bt = block_tables + (int64_t)b * max_pages_per_seq;
-    const int last_page = (n_total - 1) / 16;
     // token of this lane's row in score tile t: (r16/4)*8 + t*4 + r16%4
     const int krow0 = (r16 >> 2) * 8 + (r16 & 3);
-    // The wave's page ids (at most span_len/64 + 1 <= 17) are fetched once, lane i holding the
-    // i-th; the loop reads them with v_readlane, so no table load sits between two blocks.
-    // Entries past the last valid page are clamped to it: they are never dereferenced otherwise.
-    const int page_base = t_begin >> 4;
-    const int my_pages = bt[min(page_base + lane, last_page)];
+    // The span's page ids sit one per lane; the loop reads them with v_readlane, so no table load
+    // sits between two blocks.  Entries past the request's last page were clamped to it by the
+    // planner; the second page of a span's last block is clamped to the span's last entry here.
+    const int page_base = s_begin >> 4;
 
     // One 32-token block = the K fragments of two score tiles and the V^T fragments of all channel
     // tiles: 16 KiB per wave (head_dim 128), fetched one block ahead of the MFMAs that consume it.
@@ -131,8 +155,13 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict
     };
     auto load_block = [&](int tb, Block& blk) {
       const int pi = (tb >> 4) - page_base;
-      const int64_t page0 = __builtin_amdgcn_readlane(my_pages, pi);
-      const int64_t page1 = __builtin_amdgcn_readlane(my_pages, pi + 1);
+      const int pj = min(pi + 1, pages_per_span - 1);
+      auto page_of = [&](int i) -> int64_t {  // i is wave-uniform
+        const int r = i >> 6;
+        const int v = r == 0 ? my_pages[0] : r == 1 ? my_pages[1] : r == 2 ? my_pages[2] : my_pages[3];
+        return __builtin_amdgcn_readlane(v, i & 63);
+      };
+      const int64_t page0 = page_of(pi), page1 = page_of(pj);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int tok = krow0 + t * 4;
@@ -195,18 +224,25 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16* __restrict
       }
     };
 
-    // two blocks per trip, ping-pong between two register sets; a prefetch past the end of the
-    // wave's range re-reads its last block (valid memory, never used)
-    const int tb_last = t_begin + ((t_end - t_begin - 1) & ~31);
+    // Two blocks per trip, ping-pong between two register sets.  Every block is loaded exactly
+    // once: the steady-state loop only runs while two more blocks follow (its loads are
+    // unconditional, so the compiler's wait counts stay exact), the last one or two blocks are
+    // peeled off.
     Block b0, b1;
-    load_block(t_begin, b0);
-    for (int tb = t_begin; tb < t_end; tb += 64) {
-      load_block(min(tb + 32, tb_last), b1);
+    int tb = t_begin;
+    load_block(tb, b0);
+    for (; tb + 64 < t_end; tb += 64) {
+      load_block(tb + 32, b1);
       compute_block(tb, b0);
-      if (tb + 32 < t_end) {
-        load_block(min(tb + 64, tb_last), b0);
-        compute_block(tb + 32, b1);
-      }
+      load_block(tb + 64, b0);
+      compute_block(tb + 32, b1);
+    }
+    if (tb + 32 < t_end) {
+      load_block(tb + 32, b1);
+      compute_block(tb, b0);
+      compute_block(tb + 32, b1);
+    } else {
+      compute_block(tb, b0);
     }
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
@@ -267,45 +303,54 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
   out[operand_offset(out_lay, b, h * DH + c)] = (bf16)(num / den);
 }
 
-// Span length: long spans (fewer partials; most requests finish inside one workgroup) unless the
-// batch is so small that parallelism has to come from splitting each context.  Measured on the
-// 70B shape: 1024 beats 256 from batch 16 up.
+// Span length.  A workgroup's fixed costs (start-up, the merge of its four waves, its partial
+// result) are paid once per span, so spans should be as long as the batch allows while the launch
+// still has several workgroups per CU; a context that fits one span needs no partials at all.
+// Measured on the 70B shape (attention ms per layer at spans 256 / 1024 / 2048 / 4096): batch 16:
+// .032 / .028 / .035 / .046; batch 128: .158 / .138 / .137 / .138; batch 512: .610 / .521 / .494 / .487.
 int attn_decode_span(int batch, int n_kv_heads) {
-  if (const char* e = getenv("TDP_ATTN_SPAN")) {  // tuning aid: 256, 512 or 1024
+  if (const char* e = getenv("TDP_ATTN_SPAN")) {  // tuning aid
     const int v = atoi(e);
-    if (v == 256 || v == 512 || v == 1024) return v;
+    if (v == 256 || v == 512 || v == 1024 || v == 2048 || v == 4096) return v;
   }
-  return batch * n_kv_heads >= 128 ? kDecodeSpanMax : kDecodeSpanMin;
+  const int units = batch * n_kv_heads;
+  return units >= 4096 ? 4096 : units >= 1024 ? 2048 : units >= 128 ? 1024 : kDecodeSpanMin;
 }
 
-hipError_t launch_attn_plan(const int32_t* ctx_lens, int batch, int span_len, int2* items, int32_t* n_items,
+int attn_decode_items(int batch, int max_spans, int span_len) {
+  // max_spans counts spans of the minimum length; longer spans need proportionally fewer slots
+  return batch * ((max_spans * kDecodeSpanMin + span_len - 1) / span_len);
+}
+
+hipError_t launch_attn_plan(const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq, int batch,
+                            int max_spans, int span_len, int4* items, int32_t* n_items, int32_t* item_pages,
                             hipStream_t s) {
   if (batch <= 0) return hipSuccess;
-  attn_plan_kernel<<<1, 256, 0, s>>>(ctx_lens, batch, span_len, items, n_items);
+  const int max_items = attn_decode_items(batch, max_spans, span_len);
+  attn_plan_kernel<<<1, 256, 0, s>>>(ctx_lens, batch, span_len, items, max_items, n_items);
+  attn_plan_pages_kernel<<<max_items, 64, 0, s>>>(items, block_tables, max_pages_per_seq, span_len / 16, item_pages);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
-                              const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq,
-                              const int2* items, const int32_t* n_items, float* part_o, float* part_ml,
-                              int max_spans, int span_len, void* out, OperandLayout out_layout, hipStream_t s) {
+                              const int32_t* ctx_lens, const int4* items, const int32_t* item_pages, float* part_o,
+                              float* part_ml, int max_spans, int span_len, void* out, OperandLayout out_layout,
+                              hipStream_t s) {
   if (batch <= 0) return hipSuccess;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
-  // max_spans counts spans of the minimum length; longer spans need proportionally fewer slots
-  const int spans = (max_spans * kDecodeSpanMin + span_len - 1) / span_len;
-  const unsigned grid = (unsigned)batch * spans * kv.n_kv_heads;
+  const int max_items = attn_decode_items(batch, max_spans, span_len);
+  const int spans = max_items / batch;
+  const unsigned grid = (unsigned)max_items * kv.n_kv_heads;
   dim3 mgrid(n_q_heads, batch);
   if (kv.head_dim == 128) {
-    attn_decode_kernel<128><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
-                                                 max_pages_per_seq, items, n_items, part_o, part_ml, max_spans,
-                                                 span_len, (bf16*)out, out_layout, scale_log2);
+    attn_decode_kernel<128><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, items, item_pages, part_o,
+                                                 part_ml, max_spans, span_len, (bf16*)out, out_layout, scale_log2);
     if (spans > 1)
       attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
                                                           span_len, (bf16*)out, out_layout);
   } else {
-    attn_decode_kernel<64><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, ctx_lens, block_tables,
-                                                max_pages_per_seq, items, n_items, part_o, part_ml, max_spans,
-                                                span_len, (bf16*)out, out_layout, scale_log2);
+    attn_decode_kernel<64><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, items, item_pages, part_o,
+                                                part_ml, max_spans, span_len, (bf16*)out, out_layout, scale_log2);
     if (spans > 1)
       attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
                                                         span_len, (bf16*)out, out_layout);

@@ -50,8 +50,9 @@ struct tdp_stage {
   float* ws = nullptr;
   int64_t ws_elems = 0;
   float *part_o = nullptr, *part_ml = nullptr;
-  int2* attn_items = nullptr;     // decode work list, rebuilt every step
+  int4* attn_items = nullptr;     // decode work list, rebuilt every step
   int32_t* attn_n_items = nullptr;
+  int32_t* attn_item_pages = nullptr;  // physical pages of every item's span
   int max_chunks = 0;             // spans of kDecodeSpanMin tokens in the longest context
   float2* rope_table = nullptr;
   int max_pos = 0;
@@ -143,7 +144,9 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
   const void* x = hidden_in;
   int x_f32 = 0;
   const int span_len = attn_decode_span(M, c.n_kv_heads);
-  if (ctx_lens) HIP_TRY(launch_attn_plan(ctx_lens, M, span_len, st->attn_items, st->attn_n_items, s));
+  if (ctx_lens)
+    HIP_TRY(launch_attn_plan(ctx_lens, block_tables, c.max_pages_per_seq, M, st->max_chunks, span_len, st->attn_items,
+                             st->attn_n_items, st->attn_item_pages, s));
   const int l_begin = st->layer_count > 0 ? st->layer_first : 0;
   const int l_end = st->layer_count > 0 ? st->layer_first + st->layer_count : c.n_layers;
   for (int l = l_begin; l < l_end; ++l) {
@@ -177,9 +180,9 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
     {  // a4: attention
       Timer t(st, s, T_ATTN);
       if (ctx_lens)
-        HIP_TRY(launch_attn_decode(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, ctx_lens, block_tables,
-                                   c.max_pages_per_seq, st->attn_items, st->attn_n_items, st->part_o, st->part_ml,
-                                   st->max_chunks, span_len, st->attn, layout_paired(st->dq), s));
+        HIP_TRY(launch_attn_decode(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, ctx_lens, st->attn_items,
+                                   st->attn_item_pages, st->part_o, st->part_ml, st->max_chunks, span_len, st->attn,
+                                   layout_paired(st->dq), s));
       else
         HIP_TRY(launch_attn_prefill(st->qkv, st->Nqkv_pad, M, n_seqs, c.n_q_heads, kv, cu_seqlens, block_tables,
                                     c.max_pages_per_seq, st->attn, layout_paired(st->dq), s));
@@ -278,6 +281,9 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
   A(&st->part_o, (int64_t)c.max_batch * c.n_q_heads * st->max_chunks * dh, false);
   A(&st->part_ml, (int64_t)c.max_batch * c.n_q_heads * st->max_chunks * 2, false);
   A(&st->attn_items, (int64_t)c.max_batch * st->max_chunks, false);
+  // spans longer than the minimum round the span count up: up to (1024 / 256 - 1) extra minimum spans' worth
+  A(&st->attn_item_pages, (int64_t)c.max_batch * (st->max_chunks + kDecodeSpanMax / kDecodeSpanMin) * (kDecodeSpanMin / 16),
+    false);
   A(&st->attn_n_items, 1, true);
   A(&st->rope_table, (int64_t)st->max_pos * (dh / 2), false);
   if (e == hipSuccess) {
@@ -306,7 +312,7 @@ void tdp_stage_destroy(tdp_stage* st) {
   (void)hipDeviceSynchronize();
   void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->bqkv, st->kpool, st->vpool, st->y,
                   st->qkv, st->attn, st->h, st->u, st->xa, st->xb, st->ws, st->part_o, st->part_ml,
-                  st->attn_items, st->attn_n_items, st->rope_table};
+                  st->attn_items, st->attn_n_items, st->attn_item_pages, st->rope_table};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (hipEvent_t ev : st->ev_start) (void)hipEventDestroy(ev);

@@ -90,15 +90,19 @@ hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const Kv
 
 // ---- attention -------------------------------------------------------------------------------
 // tokens of one request's context handled by one workgroup (multiples of 128: four waves, 32-token blocks)
-constexpr int kDecodeSpanMin = 256, kDecodeSpanMax = 1024;
+constexpr int kDecodeSpanMin = 256, kDecodeSpanMax = 4096;
 int attn_decode_span(int batch, int n_kv_heads);
-// once per decode step: the compact list of (request, span) work items
-hipError_t launch_attn_plan(const int32_t* ctx_lens, int batch, int span_len, int2* items, int32_t* n_items,
+// once per decode step: the compact list of work items (request, span, tokens to attend to, 0),
+// its unused tail marked with request -1 up to attn_decode_items(), and per item the physical pages
+// of its span (span_len / 16 entries each)
+int attn_decode_items(int batch, int max_spans, int span_len);
+hipError_t launch_attn_plan(const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq, int batch,
+                            int max_spans, int span_len, int4* items, int32_t* n_items, int32_t* item_pages,
                             hipStream_t s);
 hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
-                              const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq,
-                              const int2* items, const int32_t* n_items, float* part_o, float* part_ml,
-                              int max_spans, int span_len, void* out, OperandLayout out_layout, hipStream_t s);
+                              const int32_t* ctx_lens, const int4* items, const int32_t* item_pages, float* part_o,
+                              float* part_ml, int max_spans, int span_len, void* out, OperandLayout out_layout,
+                              hipStream_t s);
 hipError_t launch_attn_prefill(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
                                const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
                                int max_pages_per_seq, void* out, OperandLayout out_layout, hipStream_t s);

@@ -360,3 +360,14 @@ def test_a_dropped_bias_would_be_caught(tdp):
             torch.cuda.synchronize()
             outs.append(f64(out))
     assert row_rel_err(outs[0], outs[1]) > 3 * TOL
+
+
+@pytest.mark.parametrize("span", [256, 512, 1024, 2048, 4096])
+def test_decode_every_span_length(tdp, span, monkeypatch):
+    """The library picks the span length (tokens of one context handled by one workgroup) from the
+    batch size; TDP_ATTN_SPAN forces it.  Contexts sit on and around the span boundaries, so
+    requests finish inside one workgroup, need exactly two partials, or end one token into a span."""
+    monkeypatch.setenv("TDP_ATTN_SPAN", str(span))
+    ctx = sorted({0, 31, span - 2, span - 1, span, span + 1, 2 * span - 1, 2 * span, 2 * span + 33,
+                  min(3 * span + 7, 4096)} & set(range(0, 4097)))
+    run_decode_case(tdp, "tiny_gqa", ctx, n_layers=1, max_pages_per_seq=4096 // 16 + 1)
