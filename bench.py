@@ -313,16 +313,18 @@ def main():
     work = A.decode_step_work(*sargs, dec_ctx)
     log("decode B=%d: %.3f ms/step, %.0f tok/s, %.0f GB/s algorithmic" % (B, ms, B / ms * 1e3,
                                                                           work["bytes"] / ms / 1e6))
-    pct = step_percentiles(decode_fn, max(args.steps, 20))
-    # the same step repeated rewrites the same KV slot; this run advances every context by one token
-    # per step instead, so each request crosses a page boundary once within ADVANCE_STEPS steps
-    ctx_run = ctx_d.clone()
+    pct, ms_adv = None, None
+    if not args.no_sweep:   # (--no-sweep is the lean mode the profiler runs use: headline + per-class times only)
+        pct = step_percentiles(decode_fn, max(args.steps, 20))
+        # the same step repeated rewrites the same KV slot; this run advances every context by one token
+        # per step instead, so each request crosses a page boundary once within ADVANCE_STEPS steps
+        ctx_run = ctx_d.clone()
 
-    def advancing_fn():
-        tdp.tdp_stage_decode(st.h, x, ctx_run, tab_d, B, out, stream)
-        ctx_run.add_(1)
+        def advancing_fn():
+            tdp.tdp_stage_decode(st.h, x, ctx_run, tab_d, B, out, stream)
+            ctx_run.add_(1)
 
-    ms_adv = time_calls(advancing_fn, 0, ADVANCE_STEPS)
+        ms_adv = time_calls(advancing_fn, 0, ADVANCE_STEPS)
     ct = class_times(tdp, st, decode_fn, 5)
     kern = kernel_rooflines(shape, B, work["kv_read_bytes"], work["attn_flops"], ct, "decode")
     workload_name = "%s stage, decode phase, batch %d" % (args.workload, B)
@@ -351,7 +353,8 @@ def main():
                    "hbm_gbs": round(work["bytes"] / ms / 1e6, 1),
                    "hbm_frac": round(work["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4),
                    "composite_t_min_ms": round(t_min, 3), "composite_frac": round(t_min / ms, 4),
-                   "step_ms_percentiles": pct, "advancing_context_ms_per_step": round(ms_adv, 4),
+                   "step_ms_percentiles": pct,
+                   "advancing_context_ms_per_step": None if ms_adv is None else round(ms_adv, 4),
                    "class_ms": {k: round(v, 4) for k, v in ct.items()}, "kernels": kern},
     }
 
@@ -410,7 +413,7 @@ def main():
 
     st.close()
     torch.cuda.empty_cache()
-    if not args.layers:
+    if not args.layers and not args.no_sweep:
         result["ends"] = ends_section(tdp, W, shape, B, i32)
         log("pipeline ends at batch %d: embedding %.3f ms, final norm + vocabulary projection + greedy %.3f ms" % (
             B, result["ends"]["embed_ms"], result["ends"]["lm_head_ms"]))
