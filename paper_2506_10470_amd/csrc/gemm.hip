@@ -382,15 +382,19 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   if (kt_end > p.k_tiles_total * 2) kt_end = p.k_tiles_total * 2;
   const int n_stages = kt_end - kt_begin;  // even: two stages per 64-wide k-tile
 
+  // DMA addressing: a wave-uniform 64-bit base per operand, which moves one k-stage per request,
+  // plus loop-invariant 32-bit per-lane byte offsets (scalar base + vector offset needs no vector
+  // arithmetic per load).
+  typedef const __attribute__((address_space(1))) char* gptr;
   const int r_in = lane / CPR;
-  unsigned a_goff[IPA], w_goff;
+  unsigned a_goff[IPA], w_goff;  // bytes
 #pragma unroll
   for (int j = 0; j < IPA; ++j) {
     const int row = (wave * IPA + j) * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
     int m = row;
     if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
-    a_goff[j] = (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + c_sw * 8);
+    a_goff[j] = 2u * (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + c_sw * 8);
   }
   // weight rows need no clamp: row block j of this wave lies j * RPI rows further on, and the
   // swizzle term (row / RW) % CPR does not depend on j (RPI is a multiple of RW * CPR)
@@ -398,31 +402,41 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   {
     const int row = wave * IPW * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
-    w_goff = (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + c_sw * 8);
+    w_goff = 2u * (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + c_sw * 8);
   }
-  const int64_t w_jstride = (int64_t)(RPI / 2) * p.w_lay.pair;
-  const bf16* a_base = p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * p.a_lay.kb;
-  const bf16* w_base = p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * p.w_lay.kb;
-  // DMA instruction j (0 .. N_DMA-1) of stage t: activations first, then weights
+  const int64_t w_jstride = (int64_t)RPI * p.w_lay.pair;  // bytes between this wave's weight row blocks
+  const int64_t a_step = 2 * p.a_lay.kb, w_step = 2 * p.w_lay.kb;  // bytes per k-stage
+  // the stage being requested: global bases, index and ring slot; past the last stage the bases
+  // stay put, so the tail re-fetches the last stage (valid memory, never read)
+  gptr a_req = (gptr)(p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * p.a_lay.kb);
+  gptr w_req = (gptr)(p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * p.w_lay.kb);
+  int req_t = 0, req_slot = 0;
   constexpr int N_DMA = IPA + IPW;
-  auto dma_one = [&](int t, int j) {
-    const int tc = t < n_stages ? t : n_stages - 1;  // the tail re-fetches the last stage (never read)
+  auto dma_one = [&](int j) {  // instruction j of the requested stage: activations first, then weights
+    unsigned char* ring = smem_raw + req_slot * (STAGE * 2);
     if (j < IPA) {
-      const bf16* ab = a_base + (int64_t)tc * p.a_lay.kb;
-      bf16* la = smem + (t % NS) * STAGE + wave * IPA * RPI * BK;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ab + a_goff[j]),
-                                       (__attribute__((address_space(3))) void*)(la + j * RPI * BK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_req + a_goff[j]),
+                                       (__attribute__((address_space(3))) void*)(ring + ((wave * IPA + j) * RPI * BK) * 2),
+                                       16, 0, 0);
     } else {
       const int jw = j - IPA;
-      const bf16* wb = w_base + (int64_t)tc * p.w_lay.kb;
-      bf16* lw = smem + (t % NS) * STAGE + BM * BK + wave * IPW * RPI * BK;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wb + jw * w_jstride + w_goff),
-                                       (__attribute__((address_space(3))) void*)(lw + jw * RPI * BK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(w_req + jw * w_jstride + w_goff),
+                                       (__attribute__((address_space(3))) void*)(ring + (BM * BK + (wave * IPW + jw) * RPI * BK) * 2),
+                                       16, 0, 0);
     }
   };
-  auto dma_stage = [&](int t) {
+  auto dma_advance = [&]() {
+    ++req_t;
+    if (req_t < n_stages) {
+      a_req += a_step;
+      w_req += w_step;
+    }
+    req_slot = req_slot + 1 == NS ? 0 : req_slot + 1;
+  };
+  auto dma_stage = [&]() {
 #pragma unroll
-    for (int j = 0; j < N_DMA; ++j) dma_one(t, j);
+    for (int j = 0; j < N_DMA; ++j) dma_one(j);
+    dma_advance();
   };
 
   f32x4 acc[WT][AT];
@@ -441,46 +455,62 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   bf16x8 wf[2][WT], af[2][AT];
   constexpr int PENDING = (NS - 2) * N_DMA;
   static_assert(WT == 8 && N_DMA <= WT && AT <= WT, "one weight tile, one DMA and at most one activation tile per MFMA group");
-  auto read_frags = [&](int t, int set) {
-    const bf16* base = smem + (t % NS) * STAGE;
+  int rd_slot = 0;  // ring slot of the stage whose fragments are read next
+  auto read_frags = [&](int set) {
+    const bf16* base = smem + rd_slot * STAGE;
 #pragma unroll
     for (int wt = 0; wt < WT; ++wt) wf[set][wt] = ld_bf16x8(base + w_off + wt * 16 * BK);
 #pragma unroll
     for (int at = 0; at < AT; ++at) af[set][at] = ld_bf16x8(base + a_off + at * 16 * BK);
   };
-  // Stage t: its fragments are in register set `set`; stage t+1 was requested NS-2 barriers ago.
-  // The MFMAs are inline assembly so that every accumulator stays in place in its AGPRs (left to
-  // itself the register allocator shuttles the 64 accumulator tuples through VGPRs); issue order
-  // is therefore explicit: eight groups of [fragment reads and one DMA of the stages ahead, the
-  // MFMAs of one weight tile], separated by scheduling barriers.
-  auto stage = [&](int t, int set) {
-    // vmcnt: this wave's loads of stage t+1 have landed; lgkmcnt: its reads of stage t are complete,
-    // so after the barrier buffer t % NS may be refilled and stage t+1 may be read
+  // One stage: its fragments are in register set `set`; the next stage was requested NS-2
+  // barriers ago.  The MFMAs are inline assembly so that every accumulator stays in place in its
+  // AGPRs (left to itself the register allocator shuttles the 64 accumulator tuples through
+  // VGPRs); issue order is therefore explicit: eight groups of MFMAs (one weight tile each), with
+  // the fragment reads and the DMA of the stages ahead slotted in behind single MFMAs and pinned
+  // by scheduling barriers.
+  auto stage = [&](int set) {
+    // vmcnt: this wave's loads of the next stage have landed; lgkmcnt: its reads of this stage are
+    // complete, so after the barrier this stage's buffer may be refilled and the next one read
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
-    const bf16* next = smem + ((t + 1) % NS) * STAGE;
+    const bf16* next = smem + rd_slot * STAGE;
 #pragma unroll
     for (int g = 0; g < WT; ++g) {
-      wf[set ^ 1][g] = ld_bf16x8(next + w_off + g * 16 * BK);
-      if (g < AT) af[set ^ 1][g] = ld_bf16x8(next + a_off + g * 16 * BK);
-      if (g < N_DMA) dma_one(t + NS, g);
-      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int at = 0; at < AT; ++at)
+      for (int at = 0; at < AT; ++at) {
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[g][at]) : "v"(wf[set][g]), "v"(af[set][at]));
-      __builtin_amdgcn_sched_barrier(0);
+        // one other instruction behind each of the group's first three MFMAs, so that each issues
+        // while the matrix pipe is busy instead of in a gap between groups
+        if (at == 0) {
+          __builtin_amdgcn_sched_barrier(0);
+          wf[set ^ 1][g] = ld_bf16x8(next + w_off + g * 16 * BK);
+          __builtin_amdgcn_sched_barrier(0);
+        } else if (at == 1 && g < AT) {
+          __builtin_amdgcn_sched_barrier(0);
+          af[set ^ 1][g] = ld_bf16x8(next + a_off + g * 16 * BK);
+          __builtin_amdgcn_sched_barrier(0);
+        } else if (at == 2 && g < N_DMA) {
+          __builtin_amdgcn_sched_barrier(0);
+          dma_one(g);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
+    dma_advance();
+    rd_slot = rd_slot + 1 == NS ? 0 : rd_slot + 1;
   };
 
   if (n_stages > 0) {
 #pragma unroll
-    for (int t = 0; t < NS - 1; ++t) dma_stage(t);
+    for (int t = 0; t < NS - 1; ++t) dma_stage();
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
-    read_frags(0, 0);
-    dma_stage(NS - 1);
+    read_frags(0);
+    rd_slot = 1 % NS;
+    dma_stage();
   }
   for (int t = 0; t < n_stages; t += 2) {
-    stage(t, 0);
-    stage(t + 1, 1);
+    stage(0);
+    stage(1);
   }
   // loads still in flight target LDS only; they must land before the workgroup's LDS is released.
   // The nops cover the MFMA -> accumulator-read distance, which the compiler cannot see.
