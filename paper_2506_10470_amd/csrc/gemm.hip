@@ -412,17 +412,22 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   gptr w_req = (gptr)(p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * p.w_lay.kb);
   int req_t = 0, req_slot = 0;
   constexpr int N_DMA = IPA + IPW;
+  // One DMA instruction: 64 lanes x 16 bytes from (scalar base + per-lane byte offset) into 1 KiB
+  // of LDS at lds_addr.  Written as assembly to get the scalar-base form (no vector address
+  // arithmetic per load); M0 carries the LDS address, and every DMA of this kernel goes through
+  // here, so nothing else depends on M0.
+  auto dma16 = [](unsigned lane_off, gptr base, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
+                 : "memory");
+  };
+  const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
   auto dma_one = [&](int j) {  // instruction j of the requested stage: activations first, then weights
-    unsigned char* ring = smem_raw + req_slot * (STAGE * 2);
+    const unsigned ring = ring_base + req_slot * (STAGE * 2);
     if (j < IPA) {
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_req + a_goff[j]),
-                                       (__attribute__((address_space(3))) void*)(ring + ((wave * IPA + j) * RPI * BK) * 2),
-                                       16, 0, 0);
+      dma16(a_goff[j], a_req, ring + ((wave * IPA + j) * RPI * BK) * 2);
     } else {
       const int jw = j - IPA;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(w_req + jw * w_jstride + w_goff),
-                                       (__attribute__((address_space(3))) void*)(ring + (BM * BK + (wave * IPW + jw) * RPI * BK) * 2),
-                                       16, 0, 0);
+      dma16(w_goff, w_req + jw * w_jstride, ring + (BM * BK + (wave * IPW + jw) * RPI * BK) * 2);
     }
   };
   auto dma_advance = [&]() {
