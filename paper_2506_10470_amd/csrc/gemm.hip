@@ -387,49 +387,61 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   // arithmetic per load).
   typedef const __attribute__((address_space(1))) char* gptr;
   const int r_in = lane / CPR;
-  unsigned a_goff[IPA], w_goff;  // bytes
+  // Instruction j of an operand lands 1 KiB further on in LDS than instruction 0; that distance
+  // rides in the instruction's immediate offset, which also moves the global address, so it is
+  // taken out of the per-lane offsets again.  The per-lane offset is zero-extended by the hardware
+  // and must not go negative: a constant bias keeps it positive and is subtracted from the bases.
+  constexpr int kImmBias = 3 * 1024;
+  unsigned a_goff[IPA];  // bytes
 #pragma unroll
   for (int j = 0; j < IPA; ++j) {
     const int row = (wave * IPA + j) * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
     int m = row;
     if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
-    a_goff[j] = 2u * (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + c_sw * 8);
+    a_goff[j] = 2u * (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + c_sw * 8) + (unsigned)(kImmBias - j * 1024);
   }
   // weight rows need no clamp: row block j of this wave lies j * RPI rows further on, and the
   // swizzle term (row / RW) % CPR does not depend on j (RPI is a multiple of RW * CPR)
   static_assert(RPI % (RW * CPR) == 0 && RPI % 2 == 0, "swizzle and row parity repeat per row block");
+  unsigned w_goff[IPW];
   {
     const int row = wave * IPW * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
-    w_goff = 2u * (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + c_sw * 8);
+    const unsigned w0 = 2u * (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + c_sw * 8);
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) w_goff[j] = w0 + (unsigned)(j * RPI * p.w_lay.pair) + (unsigned)(kImmBias - j * 1024);
   }
-  const int64_t w_jstride = (int64_t)RPI * p.w_lay.pair;  // bytes between this wave's weight row blocks
   const int64_t a_step = 2 * p.a_lay.kb, w_step = 2 * p.w_lay.kb;  // bytes per k-stage
   // the stage being requested: global bases, index and ring slot; past the last stage the bases
   // stay put, so the tail re-fetches the last stage (valid memory, never read)
-  gptr a_req = (gptr)(p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * p.a_lay.kb);
-  gptr w_req = (gptr)(p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * p.w_lay.kb);
+  gptr a_req = (gptr)(p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * p.a_lay.kb) - kImmBias;
+  gptr w_req = (gptr)(p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * p.w_lay.kb) - kImmBias;
   int req_t = 0, req_slot = 0;
   constexpr int N_DMA = IPA + IPW;
   // One DMA instruction: 64 lanes x 16 bytes from (scalar base + per-lane byte offset) into 1 KiB
   // of LDS at lds_addr.  Written as assembly to get the scalar-base form (no vector address
   // arithmetic per load); M0 carries the LDS address, and every DMA of this kernel goes through
   // here, so nothing else depends on M0.
-  auto dma16 = [](unsigned lane_off, gptr base, unsigned lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
-                 : "memory");
-  };
+  auto dma_aim = [](unsigned lds_addr) { asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(lds_addr) : "memory"); };
+#define TDP_DMA16(lane_off, base, imm) \
+  asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(lane_off), "s"(base), "n"(imm) : "memory")
   const unsigned ring_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
-  auto dma_one = [&](int j) {  // instruction j of the requested stage: activations first, then weights
+  static_assert(IPA <= 4 && IPW <= 4, "immediate offsets up to 3 KiB");
+  // instruction j of the requested stage: activations first, then weights; M0 is aimed at the
+  // wave's first KiB of each operand once per stage
+  auto dma_one = [&](int j) {
     const unsigned ring = ring_base + req_slot * (STAGE * 2);
-    if (j < IPA) {
-      dma16(a_goff[j], a_req, ring + ((wave * IPA + j) * RPI * BK) * 2);
-    } else {
-      const int jw = j - IPA;
-      dma16(w_goff, w_req + jw * w_jstride, ring + (BM * BK + (wave * IPW + jw) * RPI * BK) * 2);
+    if (j == 0) dma_aim(ring + (wave * IPA * RPI * BK) * 2);
+    if (j == IPA) dma_aim(ring + (BM * BK + wave * IPW * RPI * BK) * 2);
+    switch (j < IPA ? j : j - IPA) {
+      case 0: if (j < IPA) TDP_DMA16(a_goff[0], a_req, 0); else TDP_DMA16(w_goff[0], w_req, 0); break;
+      case 1: if (j < IPA) TDP_DMA16(a_goff[1 % IPA], a_req, 1024); else TDP_DMA16(w_goff[1 % IPW], w_req, 1024); break;
+      case 2: if (j < IPA) TDP_DMA16(a_goff[2 % IPA], a_req, 2048); else TDP_DMA16(w_goff[2 % IPW], w_req, 2048); break;
+      default: if (j < IPA) TDP_DMA16(a_goff[3 % IPA], a_req, 3072); else TDP_DMA16(w_goff[3 % IPW], w_req, 3072); break;
     }
   };
+#undef TDP_DMA16
   auto dma_advance = [&]() {
     ++req_t;
     if (req_t < n_stages) {
