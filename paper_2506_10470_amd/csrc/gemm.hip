@@ -473,6 +473,7 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   constexpr int PENDING = (NS - 2) * N_DMA;
   static_assert(WT == 8 && N_DMA <= WT && AT <= WT, "one weight tile, one DMA and at most one activation tile per MFMA group");
   int rd_slot = 0;  // ring slot of the stage whose fragments are read next
+  int w_next = w_off, a_next = a_off;  // this lane's fragments in that slot (element offsets into smem)
   auto read_frags = [&](int set) {
     const bf16* base = smem + rd_slot * STAGE;
 #pragma unroll
@@ -490,31 +491,55 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
     // vmcnt: this wave's loads of the next stage have landed; lgkmcnt: its reads of this stage are
     // complete, so after the barrier this stage's buffer may be refilled and the next one read
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
-    const bf16* next = smem + rd_slot * STAGE;
 #pragma unroll
     for (int g = 0; g < WT; ++g) {
 #pragma unroll
       for (int at = 0; at < AT; ++at) {
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[g][at]) : "v"(wf[set][g]), "v"(af[set][at]));
-        // one other instruction behind each of the group's first three MFMAs, so that each issues
-        // while the matrix pipe is busy instead of in a gap between groups
+        // everything that is not an MFMA goes behind single MFMAs, a few instructions at a time, so
+        // that it issues while the matrix pipe is busy instead of in a gap of the MFMA stream
         if (at == 0) {
           __builtin_amdgcn_sched_barrier(0);
-          wf[set ^ 1][g] = ld_bf16x8(next + w_off + g * 16 * BK);
+          wf[set ^ 1][g] = ld_bf16x8(smem + w_next + g * 16 * BK);
           __builtin_amdgcn_sched_barrier(0);
         } else if (at == 1 && g < AT) {
           __builtin_amdgcn_sched_barrier(0);
-          af[set ^ 1][g] = ld_bf16x8(next + a_off + g * 16 * BK);
+          af[set ^ 1][g] = ld_bf16x8(smem + a_next + g * 16 * BK);
           __builtin_amdgcn_sched_barrier(0);
         } else if (at == 2 && g < N_DMA) {
           __builtin_amdgcn_sched_barrier(0);
           dma_one(g);
           __builtin_amdgcn_sched_barrier(0);
         }
+        // the stage's bookkeeping, behind MFMAs of the last group that carry nothing else: the
+        // request side moves on one stage, and so do the fragment offsets.  (The empty statements
+        // make the new values exist here rather than wherever their next use is.)
+        if (g == WT - 1 && at == 3) {
+          __builtin_amdgcn_sched_barrier(0);
+          ++req_t;
+          if (req_t < n_stages) {
+            a_req += a_step;
+            w_req += w_step;
+          }
+          asm volatile("" : "+s"(a_req), "+s"(w_req), "+s"(req_t));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (g == WT - 1 && at == (AT > 4 ? 4 : 3)) {
+          __builtin_amdgcn_sched_barrier(0);
+          req_slot = req_slot + 1 == NS ? 0 : req_slot + 1;
+          rd_slot = rd_slot + 1 == NS ? 0 : rd_slot + 1;
+          asm volatile("" : "+s"(req_slot), "+s"(rd_slot));
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (g == WT - 1 && at == (AT > 5 ? 5 : 3)) {
+          __builtin_amdgcn_sched_barrier(0);
+          w_next = rd_slot * STAGE + w_off;
+          a_next = rd_slot * STAGE + a_off;
+          asm volatile("" : "+v"(w_next), "+v"(a_next));
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
     }
-    dma_advance();
-    rd_slot = rd_slot + 1 == NS ? 0 : rd_slot + 1;
   };
 
   if (n_stages > 0) {
@@ -523,6 +548,8 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
     read_frags(0);
     rd_slot = 1 % NS;
+    w_next = rd_slot * STAGE + w_off;
+    a_next = rd_slot * STAGE + a_off;
     dma_stage();
   }
   for (int t = 0; t < n_stages; t += 2) {
