@@ -35,6 +35,8 @@ from typing import Iterable, List, Optional, Sequence, Tuple
 
 import numpy as np
 
+from .fp8_oracle import kv_roundtrip
+
 F64 = np.float64
 
 
@@ -65,6 +67,9 @@ class Shape:
     head_dim: int
     rms_eps: float = 1e-5
     rope_base: float = 10000.0
+    # 8-bit KV cache option (fp8_oracle.py): (k_scale, v_scale), or None for a cache that stores
+    # keys and values as they are.
+    kv_scales: Optional[Tuple[float, float]] = None
 
 
 def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
@@ -125,11 +130,16 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, p0: int, sh: Shape) -
 
 
 def layer_forward(x: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, w: LayerWeights,
-                  sh: Shape) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+                  sh: Shape, attend_stored: bool = False) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """One decoder layer for ONE request.
     x: [L, d] new tokens at positions p0..p0+L-1 where p0 = len(k_cache);
     k_cache, v_cache: [p0, Hkv, dh] (keys stored after rotation).
-    Returns (x_next [L, d], k_all [p0+L, Hkv, dh], v_all)."""
+    Returns (x_next [L, d], k_all [p0+L, Hkv, dh], v_all).
+    With an 8-bit cache (sh.kv_scales) the returned lists hold what the cache holds: the new
+    tokens' keys and values after the round trip through the format.  attend_stored says which
+    version the new tokens' own attention sees: False (prefill: keys and values are used as
+    computed, the cache is only written) or True (decode: the step appends to the cache first and
+    attends to the cache, Sec. 2.1)."""
     x = np.asarray(x, F64)
     L = x.shape[0]
     p0 = k_cache.shape[0]
@@ -147,9 +157,17 @@ def layer_forward(x: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, w: La
     v = v.reshape(L, sh.n_kv_heads, sh.head_dim)
     q = rope(q, pos, sh.rope_base)
     k = rope(k, pos, sh.rope_base)
-    k_all = np.concatenate([np.asarray(k_cache, F64), k], axis=0)
-    v_all = np.concatenate([np.asarray(v_cache, F64), v], axis=0)
-    a = attention(q, k_all, v_all, p0, sh)
+    if sh.kv_scales is None:
+        k_st, v_st = k, v
+    else:
+        k_st, v_st = kv_roundtrip(k, sh.kv_scales[0]), kv_roundtrip(v, sh.kv_scales[1])
+    k_all = np.concatenate([np.asarray(k_cache, F64), k_st], axis=0)
+    v_all = np.concatenate([np.asarray(v_cache, F64), v_st], axis=0)
+    if attend_stored:
+        a = attention(q, k_all, v_all, p0, sh)
+    else:
+        a = attention(q, np.concatenate([np.asarray(k_cache, F64), k], axis=0),
+                      np.concatenate([np.asarray(v_cache, F64), v], axis=0), p0, sh)
     h = x + a @ w.wo
     y2 = rmsnorm(h, w.g_mlp, sh.rms_eps)
     u = silu(y2 @ w.wg) * (y2 @ w.wu)
@@ -161,7 +179,7 @@ def empty_cache(sh: Shape) -> np.ndarray:
 
 
 def stage_forward(x: np.ndarray, caches: Optional[Sequence[Tuple[np.ndarray, np.ndarray]]],
-                  layers: Iterable[LayerWeights], sh: Shape
+                  layers: Iterable[LayerWeights], sh: Shape, attend_stored: bool = False
                   ) -> Tuple[np.ndarray, List[Tuple[np.ndarray, np.ndarray]]]:
     """The whole stage for ONE request: L new tokens through every layer.
     caches[l] = (k, v) held for layer l before the call (None = empty: prefill).
@@ -173,7 +191,7 @@ def stage_forward(x: np.ndarray, caches: Optional[Sequence[Tuple[np.ndarray, np.
             kc, vc = empty_cache(sh), empty_cache(sh)
         else:
             kc, vc = caches[li]
-        x, k_all, v_all = layer_forward(x, kc, vc, w, sh)
+        x, k_all, v_all = layer_forward(x, kc, vc, w, sh, attend_stored)
         new_caches.append((k_all, v_all))
     return x, new_caches
 
@@ -195,7 +213,7 @@ def stage_decode(xs: Sequence[np.ndarray], caches: Sequence[Sequence[Tuple[np.nd
     len(cache_b); attention covers the cache plus the token itself."""
     outs, new = [], []
     for x, c in zip(xs, caches):
-        o, nc = stage_forward(np.asarray(x, F64)[None, :], c, layers, sh)
+        o, nc = stage_forward(np.asarray(x, F64)[None, :], c, layers, sh, attend_stored=True)
         outs.append(o[0])
         new.append(nc)
     return outs, new
