@@ -20,16 +20,25 @@ class DevMem:
 def dev_view_bf16(ptr: int, nbytes: int) -> torch.Tensor:
     return torch.as_tensor(DevMem(ptr, nbytes // 2), device="cuda").view(torch.bfloat16)
 
+
+def dev_view_u8(ptr: int, nbytes: int) -> torch.Tensor:
+    return torch.as_tensor(DevMem(ptr, nbytes, "|u1"), device="cuda")
+
 class Stage:
     def __init__(self, tdp, shape: W.StageShape, num_pages: int, max_batch: int, max_tokens: int,
-                 max_seqs: int, max_pages_per_seq: int, weight_dtype=torch.bfloat16, load_weights=True):
+                 max_seqs: int, max_pages_per_seq: int, weight_dtype=torch.bfloat16, load_weights=True,
+                 kv_scales=None):
+        """kv_scales: None = bf16 KV pools; (k_scale, v_scale) = 8-bit (E4M3) pools with those scales."""
         self.tdp = tdp
         self.shape = shape
+        self.kv_scales = kv_scales
         self.cfg = tdp.StageConfig(
             n_layers=shape.n_layers, d_model=shape.d_model, n_q_heads=shape.n_q_heads,
             n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, d_ff=shape.d_ff, rms_eps=shape.rms_eps,
             rope_base=shape.rope_base, page_size=shape.page_size, num_pages=num_pages, max_batch=max_batch,
-            max_tokens=max_tokens, max_seqs=max_seqs, max_pages_per_seq=max_pages_per_seq)
+            max_tokens=max_tokens, max_seqs=max_seqs, max_pages_per_seq=max_pages_per_seq,
+            kv_dtype=tdp.KV_BF16 if kv_scales is None else tdp.KV_FP8_E4M3,
+            k_scale=0.0 if kv_scales is None else kv_scales[0], v_scale=0.0 if kv_scales is None else kv_scales[1])
         self.h = tdp.tdp_stage_create(self.cfg)
         self.num_pages = num_pages
         self.max_pages_per_seq = max_pages_per_seq
@@ -48,18 +57,22 @@ class Stage:
                 del w
 
     def pools(self, layer):
-        """(K [pages, Hkv, 16, dh], V [pages, Hkv, dh, 16]) zero-copy bf16 views."""
+        """(K [pages, Hkv, 16, dh], V [pages, Hkv, dh, 16]) zero-copy views: bf16, or the raw codes
+        (uint8) of an 8-bit cache."""
         k, v, n = self.tdp.tdp_stage_kv_pool(self.h, layer)
         sh = self.shape
-        kt = dev_view_bf16(k, n).view(self.num_pages, sh.n_kv_heads, 16, sh.head_dim)
-        vt = dev_view_bf16(v, n).view(self.num_pages, sh.n_kv_heads, sh.head_dim, 16)
+        view = dev_view_bf16 if self.kv_scales is None else dev_view_u8
+        kt = view(k, n).view(self.num_pages, sh.n_kv_heads, 16, sh.head_dim)
+        vt = view(v, n).view(self.num_pages, sh.n_kv_heads, sh.head_dim, 16)
         return kt, vt
+
+    POISON_CODE = 0x7F   # the NaN of the 8-bit format
 
     def poison(self):
         for l in range(self.shape.n_layers):
             k, v = self.pools(l)
-            k.fill_(float("nan"))
-            v.fill_(float("nan"))
+            k.fill_(float("nan") if self.kv_scales is None else self.POISON_CODE)
+            v.fill_(float("nan") if self.kv_scales is None else self.POISON_CODE)
         torch.cuda.synchronize()
 
     def close(self):

@@ -61,6 +61,10 @@ extern "C" {
 #define TDP_HOST    0
 #define TDP_DEVICE  1
 
+/* element type of the KV pools (tdp_stage_config.kv_dtype) */
+#define TDP_KV_BF16      0
+#define TDP_KV_FP8_E4M3  1   /* OCP 8-bit float, 4 exponent bits (bias 7), 3 mantissa bits, max 448, no infinities */
+
 typedef struct tdp_stage tdp_stage;   /* opaque: owns weights, KV pools and scratch (all in HBM) */
 
 typedef struct tdp_stage_config {
@@ -78,6 +82,15 @@ typedef struct tdp_stage_config {
   int32_t max_tokens;          /* largest packed prefill token count */
   int32_t max_seqs;            /* largest number of prompts in one prefill */
   int32_t max_pages_per_seq;   /* width of a block-table row */
+  /* KV-cache element type.  The decode phase is bound by reading the cache (Sec. 2.1); the paper keeps
+   * it in the model's 16-bit type (TDP_KV_BF16, the default and what every headline number uses).
+   * TDP_KV_FP8_E4M3 stores each key (after rotation) and value as the E4M3 code of value / scale:
+   * round to nearest, ties to the even code, magnitudes from 448 up saturate, NaN stays NaN; the
+   * quotient is an fp32 division.  Attention in both phases reads the cache, i.e. code * scale (the
+   * code value is exact in bf16; the scales join the softmax scale and the final normalisation), and
+   * is otherwise unchanged.  k_scale / v_scale: per stage, > 0; 0 means 1. */
+  int32_t kv_dtype;
+  float   k_scale, v_scale;
 } tdp_stage_config;
 
 /* Version of this ABI (bumped on incompatible change). */
@@ -108,8 +121,9 @@ TDP_API int tdp_stage_set_weight(tdp_stage* st, int32_t layer, int32_t which, co
 
 /*
  * Raw access to one layer's KV pools, for tests that poison, inject or dump them.
- * Layout (bf16):  K pool [num_pages][n_kv_heads][16][head_dim]
- *                 V pool [num_pages][n_kv_heads][head_dim][16]   (token slot fastest)
+ * Layout:  K pool [num_pages][n_kv_heads][16][head_dim]
+ *          V pool [num_pages][n_kv_heads][head_dim][16]   (token slot fastest)
+ * of bf16 elements, or of one-byte E4M3 codes when kv_dtype = TDP_KV_FP8_E4M3.
  * Keys are stored after the rotary embedding.  `*bytes` = size of EACH pool.
  */
 TDP_API int tdp_stage_kv_pool(tdp_stage* st, int32_t layer, void** k_dev, void** v_dev, int64_t* bytes);
@@ -120,7 +134,9 @@ TDP_API int tdp_stage_kv_pool(tdp_stage* st, int32_t layer, void** k_dev, void**
  * sequences' tokens concatenated; token t of sequence s (cu_seqlens[s] <= t < cu_seqlens[s+1])
  * lives at position t - cu_seqlens[s], i.e. page block_tables[s][pos/16], slot pos%16.
  * cu_seqlens: dev int32 [n_seqs+1]; block_tables: dev int32 [n_seqs][max_pages_per_seq].
- * import writes pages from the packed arrays, export reads pages into them.
+ * import writes pages from the packed arrays, export reads pages into them.  With an 8-bit cache
+ * the packed side stays bf16: import stores the code of value / scale, export returns
+ * bf16(code * scale).
  */
 TDP_API int tdp_stage_kv_import(tdp_stage* st, int32_t layer, const void* k_packed, const void* v_packed,
                         const int32_t* cu_seqlens, const int32_t* block_tables, int32_t n_seqs,
@@ -177,6 +193,16 @@ TDP_API int tdp_stage_set_layer_range(tdp_stage* st, int32_t first, int32_t coun
  */
 TDP_API int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out, int32_t M, int32_t N,
                   int32_t K, int32_t epilogue, int32_t tile, int32_t splits, void* stream);
+
+/*
+ * Diagnostics for the 8-bit cache format: the conversions exactly as the KV kernels perform them.
+ * tdp_e4m3_from_f32: codes[i] = E4M3 code of src[i] / scale (dev fp32 -> dev bytes; scale > 0).
+ * tdp_e4m3_to_f32:   dst[i] = value of codes[i] (dev bytes -> dev fp32), through the conversion
+ *                    instruction the decode-attention kernel uses; n a multiple of 4, codes 4-byte
+ *                    and dst 16-byte aligned.
+ */
+TDP_API int tdp_e4m3_from_f32(const float* src, uint8_t* codes, int64_t n, float scale, void* stream);
+TDP_API int tdp_e4m3_to_f32(const uint8_t* codes, float* dst, int64_t n, void* stream);
 
 /*
  * Timing hooks: when enabled, prefill/decode record HIP events around each kernel class on the

@@ -130,16 +130,15 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, p0: int, sh: Shape) -
 
 
 def layer_forward(x: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, w: LayerWeights,
-                  sh: Shape, attend_stored: bool = False) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+                  sh: Shape) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """One decoder layer for ONE request.
     x: [L, d] new tokens at positions p0..p0+L-1 where p0 = len(k_cache);
     k_cache, v_cache: [p0, Hkv, dh] (keys stored after rotation).
     Returns (x_next [L, d], k_all [p0+L, Hkv, dh], v_all).
-    With an 8-bit cache (sh.kv_scales) the returned lists hold what the cache holds: the new
-    tokens' keys and values after the round trip through the format.  attend_stored says which
-    version the new tokens' own attention sees: False (prefill: keys and values are used as
-    computed, the cache is only written) or True (decode: the step appends to the cache first and
-    attends to the cache, Sec. 2.1)."""
+    With an 8-bit cache (sh.kv_scales) the cache is the only source of keys and values: the new
+    tokens' keys and values go through the format first, attention (prefill and decode alike, Sec.
+    2.1: prefill initialises the cache, decode reads it) sees what the cache holds, and the
+    returned lists hold that too."""
     x = np.asarray(x, F64)
     L = x.shape[0]
     p0 = k_cache.shape[0]
@@ -163,11 +162,7 @@ def layer_forward(x: np.ndarray, k_cache: np.ndarray, v_cache: np.ndarray, w: La
         k_st, v_st = kv_roundtrip(k, sh.kv_scales[0]), kv_roundtrip(v, sh.kv_scales[1])
     k_all = np.concatenate([np.asarray(k_cache, F64), k_st], axis=0)
     v_all = np.concatenate([np.asarray(v_cache, F64), v_st], axis=0)
-    if attend_stored:
-        a = attention(q, k_all, v_all, p0, sh)
-    else:
-        a = attention(q, np.concatenate([np.asarray(k_cache, F64), k], axis=0),
-                      np.concatenate([np.asarray(v_cache, F64), v], axis=0), p0, sh)
+    a = attention(q, k_all, v_all, p0, sh)
     h = x + a @ w.wo
     y2 = rmsnorm(h, w.g_mlp, sh.rms_eps)
     u = silu(y2 @ w.wg) * (y2 @ w.wu)
@@ -179,7 +174,7 @@ def empty_cache(sh: Shape) -> np.ndarray:
 
 
 def stage_forward(x: np.ndarray, caches: Optional[Sequence[Tuple[np.ndarray, np.ndarray]]],
-                  layers: Iterable[LayerWeights], sh: Shape, attend_stored: bool = False
+                  layers: Iterable[LayerWeights], sh: Shape
                   ) -> Tuple[np.ndarray, List[Tuple[np.ndarray, np.ndarray]]]:
     """The whole stage for ONE request: L new tokens through every layer.
     caches[l] = (k, v) held for layer l before the call (None = empty: prefill).
@@ -191,7 +186,7 @@ def stage_forward(x: np.ndarray, caches: Optional[Sequence[Tuple[np.ndarray, np.
             kc, vc = empty_cache(sh), empty_cache(sh)
         else:
             kc, vc = caches[li]
-        x, k_all, v_all = layer_forward(x, kc, vc, w, sh, attend_stored)
+        x, k_all, v_all = layer_forward(x, kc, vc, w, sh)
         new_caches.append((k_all, v_all))
     return x, new_caches
 
@@ -213,7 +208,7 @@ def stage_decode(xs: Sequence[np.ndarray], caches: Sequence[Sequence[Tuple[np.nd
     len(cache_b); attention covers the cache plus the token itself."""
     outs, new = [], []
     for x, c in zip(xs, caches):
-        o, nc = stage_forward(np.asarray(x, F64)[None, :], c, layers, sh, attend_stored=True)
+        o, nc = stage_forward(np.asarray(x, F64)[None, :], c, layers, sh)
         outs.append(o[0])
         new.append(nc)
     return outs, new

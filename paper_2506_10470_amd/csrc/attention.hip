@@ -93,16 +93,25 @@ __global__ __launch_bounds__(64) void attn_plan_pages_kernel(const int4* __restr
   }
 }
 
-template <int DH>
+// KV8 = the pools hold E4M3 codes (one byte per element) instead of bf16.  A 16-byte load then carries
+// 16 elements, which become two MFMA operands after conversion, so the block grows to 64 tokens
+// (four pages) and the assignment of MFMA k-indices to channels (scores) and of score rows to
+// tokens changes with it; the arithmetic after the conversion is the bf16 kernel's.  The cache
+// scales ride along for free: k_scale in the softmax scale, v_scale in the final division.
+template <int DH, bool KV8>
 __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
                                                           int n_q_heads, KvLayout kv,
                                                           const int4* __restrict__ items,
                                                           const int32_t* __restrict__ item_pages,
                                                           float* __restrict__ part_o, float* __restrict__ part_ml,
                                                           int max_spans, int span_len, bf16* __restrict__ out,
-                                                          OperandLayout out_lay, float scale_log2) {
-  constexpr int KS = DH / 32;   // k-steps of the score MFMA
-  constexpr int DT = DH / 16;   // 16-channel tiles of the output
+                                                          OperandLayout out_lay, float scale_log2, float out_scale) {
+  constexpr int KS = DH / 32;          // k-steps of the score MFMA
+  constexpr int DT = DH / 16;          // 16-channel tiles of the output
+  constexpr int BT = KV8 ? 64 : 32;    // tokens per block
+  constexpr int NT = BT / 16;          // score tiles per block
+  constexpr int NP = BT / 32;          // k-steps of the output MFMA per block
+  constexpr int LT = BT / 4;           // consecutive tokens of a block whose scores end up in one lane
   const int Hkv = kv.n_kv_heads;
   const int item = blockIdx.x / Hkv, kvh = blockIdx.x % Hkv;
   // the two look-ups a workgroup starts with are independent of each other: its work record and
@@ -123,16 +132,24 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
   const int r16 = lane & 15, kg = lane >> 4;
   const bf16* kpool = (const bf16*)kv.k_pool;
   const bf16* vpool = (const bf16*)kv.v_pool;
-  // this wave's share of the span, in whole 32-token blocks
-  const int n_blocks = (s_end - s_begin + 31) >> 5;
-  const int t_begin = s_begin + 32 * ((wave * n_blocks) >> 2);
-  const int t_end = min(s_begin + 32 * (((wave + 1) * n_blocks) >> 2), s_end);
+  const uint8_t* kpool8 = (const uint8_t*)kv.k_pool;
+  const uint8_t* vpool8 = (const uint8_t*)kv.v_pool;
+  // this wave's share of the span, in whole blocks
+  const int n_blocks = (s_end - s_begin + BT - 1) / BT;
+  const int t_begin = s_begin + BT * ((wave * n_blocks) >> 2);
+  const int t_end = min(s_begin + BT * (((wave + 1) * n_blocks) >> 2), s_end);
 
+  // Query fragments.  bf16 pools: k-step kk covers channels kk*32 + kg*8 .. +8.  8-bit pools: a
+  // lane's 16-byte key load covers channels ld*64 + kg*16 .. +16, whose halves feed k-steps 2 ld and
+  // 2 ld + 1, so the query is gathered in that order.
   bf16x8 qf[KS];
   {
-    const bf16* qp = qkv + (int64_t)b * ld + (int64_t)(kvh * G + (r16 < G ? r16 : 0)) * DH + kg * 8;
+    const bf16* qp = qkv + (int64_t)b * ld + (int64_t)(kvh * G + (r16 < G ? r16 : 0)) * DH;
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) qf[kk] = r16 < G ? ld_bf16x8(qp + kk * 32) : zero_bf16x8();
+    for (int kk = 0; kk < KS; ++kk) {
+      const int ch = KV8 ? (kk >> 1) * 64 + kg * 16 + (kk & 1) * 8 : kk * 32 + kg * 8;
+      qf[kk] = r16 < G ? ld_bf16x8(qp + ch) : zero_bf16x8();
+    }
   }
   f32x4 o[DT];
 #pragma unroll
@@ -140,54 +157,80 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
   float m = kNegBig, lsum = 0.f;
 
   if (t_begin < t_end) {
-    // token of this lane's row in score tile t: (r16/4)*8 + t*4 + r16%4
-    const int krow0 = (r16 >> 2) * 8 + (r16 & 3);
+    // token (within its block) of this lane's row in score tile t: (r16/4)*LT + t*4 + r16%4; the
+    // lane's own accumulator elements are then tokens kg*LT + t*4 + i, i.e. LT consecutive tokens
+    const int krow0 = (r16 >> 2) * LT + (r16 & 3);
     // The span's page ids sit one per lane; the loop reads them with v_readlane, so no table load
     // sits between two blocks.  Entries past the request's last page were clamped to it by the
-    // planner; the second page of a span's last block is clamped to the span's last entry here.
+    // planner; pages of a span's last block that lie past the span are clamped to its last entry here.
     const int page_base = s_begin >> 4;
 
-    // One 32-token block = the K fragments of two score tiles and the V^T fragments of all channel
-    // tiles: 16 KiB per wave (head_dim 128), fetched one block ahead of the MFMAs that consume it.
+    // One block = the K fragments of NT score tiles and the V^T fragments of all channel tiles:
+    // 16 KiB per wave (head_dim 128), fetched one block ahead of the MFMAs that consume it.
     struct Block {
-      bf16x8 kf[2][KS];
-      bf16x8 vf[DT];
+      bf16x8 kf[2][KS];  // bf16 pools: [score tile][k-step]; 8-bit pools: 16 raw bytes per entry, [t / 2][(t % 2) * KS/2 + ld]
+      bf16x8 vf[DT];     // bf16 pools: 8 tokens of a channel; 8-bit pools: 16 raw bytes = 16 tokens of a channel
     };
     auto load_block = [&](int tb, Block& blk) {
       const int pi = (tb >> 4) - page_base;
-      const int pj = min(pi + 1, pages_per_span - 1);
       auto page_of = [&](int i) -> int64_t {  // i is wave-uniform
         const int r = i >> 6;
         const int v = r == 0 ? my_pages[0] : r == 1 ? my_pages[1] : r == 2 ? my_pages[2] : my_pages[3];
         return __builtin_amdgcn_readlane(v, i & 63);
       };
-      const int64_t page0 = page_of(pi), page1 = page_of(pj);
+      int64_t page[BT / 16];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int tok = krow0 + t * 4;
-        const int64_t page = tok < 16 ? page0 : page1;
-        const bf16* kp = kpool + ((page * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
+      for (int j = 0; j < BT / 16; ++j) page[j] = page_of(min(pi + j, pages_per_span - 1));
+      if constexpr (KV8) {
+        // score tile t, row r16 -> token (r16/4)*16 + t*4 + r16%4: page r16/4 of the block, slot t*4 + r16%4
+        const int64_t kpage = (r16 >> 2) == 0 ? page[0] : (r16 >> 2) == 1 ? page[1] : (r16 >> 2) == 2 ? page[2] : page[3];
+        const uint8_t* kp = kpool8 + ((kpage * Hkv + kvh) * 16 + (r16 & 3)) * DH + kg * 16;
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8(kp + kk * 32);
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int l = 0; l < KS / 2; ++l)
+            blk.kf[t >> 1][(t & 1) * (KS / 2) + l] = *reinterpret_cast<const bf16x8*>(kp + (t * 4) * DH + l * 64);
+        // channel r16 of tile d, the 16 tokens of page kg of the block
+        const int64_t vpage = kg == 0 ? page[0] : kg == 1 ? page[1] : kg == 2 ? page[2] : page[3];
+        const uint8_t* vp = vpool8 + ((vpage * Hkv + kvh) * DH + r16) * 16;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) blk.vf[d] = *reinterpret_cast<const bf16x8*>(vp + d * 16 * 16);
+      } else {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const int tok = krow0 + t * 4;
+          const bf16* kp = kpool + ((page[tok >> 4 & 1] * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8(kp + kk * 32);
+        }
+        const bf16* vp = vpool + ((page[kg >> 1] * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8(vp + d * 16 * 16);
       }
-      const int64_t page = kg < 2 ? page0 : page1;
-      const bf16* vp = vpool + ((page * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
-#pragma unroll
-      for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8(vp + d * 16 * 16);
     };
     auto compute_block = [&](int tb, Block& blk) {
-      f32x4 s[2];
+      f32x4 s[NT];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+      for (int t = 0; t < NT; ++t) {
         s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (KV8) {
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) s[t] = mfma16(blk.kf[t][kk], qf[kk], s[t]);
+          for (int l = 0; l < KS / 2; ++l) {
+            bf16x8 k0, k1;
+            e4m3x16_to_bf16x8x2(__builtin_bit_cast(uint4, blk.kf[t >> 1][(t & 1) * (KS / 2) + l]), k0, k1);
+            s[t] = mfma16(k0, qf[2 * l], s[t]);
+            s[t] = mfma16(k1, qf[2 * l + 1], s[t]);
+          }
+        } else {
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk) s[t] = mfma16(blk.kf[t][kk], qf[kk], s[t]);
+        }
       }
-      // lane holds tokens tb + kg*8 + t*4 + i of column q = r16
-      const int tok_base = tb + kg * 8;
+      // lane holds tokens tb + kg*LT + t*4 + i of column q = r16
+      const int tok_base = tb + kg * LT;
       float mx = kNegBig;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float v = (tok_base + t * 4 + i < n_total) ? s[t][i] * scale_log2 : kNegBig;
@@ -198,29 +241,47 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m, mx);
       const float alpha = exp2f(m - m_new);
-      bf16x8 pb;
+      bf16x8 pb[NP];
       float psum = 0.f;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const float pv = exp2f(s[t][i] - m_new);
           psum += pv;
-          pb[t * 4 + i] = (bf16)pv;
+          pb[t >> 1][(t & 1) * 4 + i] = (bf16)pv;
         }
       lsum = lsum * alpha + psum;
       m = m_new;
-      if (tb + 32 > n_total) {  // tail: slots past the context may hold anything, even NaN
-#pragma unroll
-        for (int d = 0; d < DT; ++d)
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (tok_base + j >= n_total) blk.vf[d][j] = (bf16)0.0f;
-      }
+      const bool tail = tb + BT > n_total;  // slots past the context may hold anything, even NaN
 #pragma unroll
       for (int d = 0; d < DT; ++d) {
         o[d] *= alpha;
-        o[d] = mfma16(blk.vf[d], pb, o[d]);
+        if constexpr (KV8) {
+          uint4 raw = __builtin_bit_cast(uint4, blk.vf[d]);
+          if (tail) {  // keep the first n_total - tok_base bytes (tokens tok_base .. tok_base + 15)
+            const int keep = min(max(n_total - tok_base, 0), 16);
+            auto mask = [&](int w) -> uint32_t {
+              const int k4 = min(max(keep - 4 * w, 0), 4);
+              return k4 == 4 ? 0xffffffffu : (1u << (8 * k4)) - 1u;
+            };
+            raw.x &= mask(0);
+            raw.y &= mask(1);
+            raw.z &= mask(2);
+            raw.w &= mask(3);
+          }
+          bf16x8 v0, v1;
+          e4m3x16_to_bf16x8x2(raw, v0, v1);
+          o[d] = mfma16(v0, pb[0], o[d]);
+          o[d] = mfma16(v1, pb[NP - 1], o[d]);
+        } else {
+          if (tail) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              if (tok_base + j >= n_total) blk.vf[d][j] = (bf16)0.0f;
+          }
+          o[d] = mfma16(blk.vf[d], pb[0], o[d]);
+        }
       }
     };
 
@@ -231,16 +292,16 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
     Block b0, b1;
     int tb = t_begin;
     load_block(tb, b0);
-    for (; tb + 64 < t_end; tb += 64) {
-      load_block(tb + 32, b1);
+    for (; tb + 2 * BT < t_end; tb += 2 * BT) {
+      load_block(tb + BT, b1);
       compute_block(tb, b0);
-      load_block(tb + 64, b0);
-      compute_block(tb + 32, b1);
+      load_block(tb + 2 * BT, b0);
+      compute_block(tb + BT, b1);
     }
-    if (tb + 32 < t_end) {
-      load_block(tb + 32, b1);
+    if (tb + BT < t_end) {
+      load_block(tb + BT, b1);
       compute_block(tb, b0);
-      compute_block(tb + 32, b1);
+      compute_block(tb + BT, b1);
     } else {
       compute_block(tb, b0);
     }
@@ -269,7 +330,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
     const float den = w0 * s_l[0][q] + w1 * s_l[1][q] + w2 * s_l[2][q] + w3 * s_l[3][q];
     const int h = kvh * G + q;
     if (n_spans == 1) {
-      out[operand_offset(out_lay, b, h * DH + c)] = (bf16)(num / den);
+      out[operand_offset(out_lay, b, h * DH + c)] = (bf16)(num / den * out_scale);
     } else {
       const int64_t slot = ((int64_t)b * n_q_heads + h) * max_spans + span;
       part_o[slot * DH + c] = num;
@@ -287,7 +348,8 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
                                                                const float* __restrict__ part_ml,
                                                                const int32_t* __restrict__ ctx_lens,
                                                                int n_q_heads, int max_spans, int span_len,
-                                                               bf16* __restrict__ out, OperandLayout out_lay) {
+                                                               bf16* __restrict__ out, OperandLayout out_lay,
+                                                               float out_scale) {
   const int h = blockIdx.x, b = blockIdx.y, c = threadIdx.x;
   const int n_spans = min((ctx_lens[b] + span_len) / span_len, max_spans);
   if (n_spans <= 1) return;  // finished by the attention kernel itself
@@ -300,7 +362,7 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
     den += w * part_ml[(base + k) * 2 + 1];
     num += w * part_o[(base + k) * DH + c];
   }
-  out[operand_offset(out_lay, b, h * DH + c)] = (bf16)(num / den);
+  out[operand_offset(out_lay, b, h * DH + c)] = (bf16)(num / den * out_scale);
 }
 
 // Span length.  A workgroup's fixed costs (start-up, the merge of its four waves, its partial
@@ -337,24 +399,29 @@ hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_he
                               float* part_ml, int max_spans, int span_len, void* out, OperandLayout out_layout,
                               hipStream_t s) {
   if (batch <= 0) return hipSuccess;
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
+  // 8-bit pools hold value / scale: the key scale joins the softmax scale, the value scale the final division
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim) * (kv.fp8 ? kv.k_scale : 1.0f);
+  const float out_scale = kv.fp8 ? kv.v_scale : 1.0f;
   const int max_items = attn_decode_items(batch, max_spans, span_len);
   const int spans = max_items / batch;
   const unsigned grid = (unsigned)max_items * kv.n_kv_heads;
   dim3 mgrid(n_q_heads, batch);
+#define TDP_DECODE(DH, KV8)                                                                                        \
+  attn_decode_kernel<DH, KV8><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, items, item_pages, part_o, \
+                                                   part_ml, max_spans, span_len, (bf16*)out, out_layout,          \
+                                                   scale_log2, out_scale)
   if (kv.head_dim == 128) {
-    attn_decode_kernel<128><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, items, item_pages, part_o,
-                                                 part_ml, max_spans, span_len, (bf16*)out, out_layout, scale_log2);
+    if (kv.fp8) TDP_DECODE(128, true); else TDP_DECODE(128, false);
     if (spans > 1)
       attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
-                                                          span_len, (bf16*)out, out_layout);
+                                                          span_len, (bf16*)out, out_layout, out_scale);
   } else {
-    attn_decode_kernel<64><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, items, item_pages, part_o,
-                                                part_ml, max_spans, span_len, (bf16*)out, out_layout, scale_log2);
+    if (kv.fp8) TDP_DECODE(64, true); else TDP_DECODE(64, false);
     if (spans > 1)
       attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
-                                                        span_len, (bf16*)out, out_layout);
+                                                        span_len, (bf16*)out, out_layout, out_scale);
   }
+#undef TDP_DECODE
   return hipGetLastError();
 }
 
@@ -374,13 +441,15 @@ hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_he
 // =====================================================================================
 constexpr float kRescaleSlack = 8.0f;  // log2 units
 
-template <int DH, int NH>
+// KV8: the pools hold E4M3 codes; a thread's chunk is then 8 bytes, converted to bf16 on its way into
+// LDS (the key scale rides in the softmax scale, the value scale in the final normalisation).
+template <int DH, int NH, bool KV8>
 __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restrict__ qkv, int64_t ld,
                                                            int n_q_heads, KvLayout kv,
                                                            const int32_t* __restrict__ cu_seqlens, int n_seqs,
                                                            const int32_t* __restrict__ block_tables,
                                                            int max_pages_per_seq, bf16* __restrict__ out,
-                                                           OperandLayout out_lay, float scale_log2) {
+                                                           OperandLayout out_lay, float scale_log2, float out_scale) {
   constexpr int NP = 256 / NH;   // query positions per workgroup
   constexpr int PB = NP / 32;    // 32-position blocks per head
   constexpr int KS = DH / 16;    // k-steps of the score MFMA
@@ -451,10 +520,28 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
       const int ci = tid + 512 * j;
       const int ksub = ci / (32 * CR), ktok = (ci / CR) % 32, kc = ci % CR;
       const int64_t kp = ksub ? (ktok < 16 ? page[2] : page[3]) : (ktok < 16 ? page[0] : page[1]);
-      kreg[j] = ld_bf16x8(kpool + ((kp * Hkv + kvh) * 16 + (ktok & 15)) * DH + kc * 8);
       const int vsub = ci / (DH * 4), vr = (ci >> 2) % DH, vc = ci & 3;
       const int64_t vp = vsub ? (vc < 2 ? page[2] : page[3]) : (vc < 2 ? page[0] : page[1]);
-      bf16x8 v = ld_bf16x8(vpool + ((vp * Hkv + kvh) * DH + vr) * 16 + (vc & 1) * 8);
+      const int64_t k_at = ((kp * Hkv + kvh) * 16 + (ktok & 15)) * DH + kc * 8;
+      const int64_t v_at = ((vp * Hkv + kvh) * DH + vr) * 16 + (vc & 1) * 8;
+      bf16x8 v;
+      if constexpr (KV8) {
+        union {
+          uint32_t u[4];
+          bf16x8 x;
+        } ck, cv;
+        const uint2 rk = *reinterpret_cast<const uint2*>((const uint8_t*)kv.k_pool + k_at);
+        const uint2 rv = *reinterpret_cast<const uint2*>((const uint8_t*)kv.v_pool + v_at);
+        e4m3x4_to_bf16x4(rk.x, ck.u[0], ck.u[1]);
+        e4m3x4_to_bf16x4(rk.y, ck.u[2], ck.u[3]);
+        e4m3x4_to_bf16x4(rv.x, cv.u[0], cv.u[1]);
+        e4m3x4_to_bf16x4(rv.y, cv.u[2], cv.u[3]);
+        kreg[j] = ck.x;
+        v = cv.x;
+      } else {
+        kreg[j] = ld_bf16x8(kpool + k_at);
+        v = ld_bf16x8(vpool + v_at);
+      }
       if (kb + 64 > L) {  // slots past the prompt may hold anything, even NaN
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -535,7 +622,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
   }
   lsum += __shfl_xor(lsum, 32, 64);
   if (qpos < L) {
-    const float inv = 1.0f / lsum;
+    const float inv = out_scale / lsum;
 #pragma unroll
     for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -553,12 +640,18 @@ template <int DH, int NH>
 static hipError_t launch_attn_prefill_t(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
                                         const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
                                         int max_pages_per_seq, void* out, OperandLayout out_layout, hipStream_t s) {
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim);
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim) * (kv.fp8 ? kv.k_scale : 1.0f);
+  const float out_scale = kv.fp8 ? kv.v_scale : 1.0f;
   constexpr int NP = 256 / NH;
   dim3 grid((total_tokens + NP - 1) / NP + n_seqs, n_q_heads / NH);
-  attn_prefill_kernel<DH, NH><<<grid, 512, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
-                                                   block_tables, max_pages_per_seq, (bf16*)out, out_layout,
-                                                   scale_log2);
+  if (kv.fp8)
+    attn_prefill_kernel<DH, NH, true><<<grid, 512, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
+                                                           block_tables, max_pages_per_seq, (bf16*)out, out_layout,
+                                                           scale_log2, out_scale);
+  else
+    attn_prefill_kernel<DH, NH, false><<<grid, 512, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, cu_seqlens, n_seqs,
+                                                            block_tables, max_pages_per_seq, (bf16*)out, out_layout,
+                                                            scale_log2, out_scale);
   return hipGetLastError();
 }
 

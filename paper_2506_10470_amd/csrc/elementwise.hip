@@ -125,20 +125,41 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(bf16* __restrict__ qkv, in
     bf16* hp = row + (int64_t)head * dh;
     const bf16x8 a = ld_bf16x8(hp + c0);
     const bf16x8 b = ld_bf16x8(hp + half + c0);
-    bf16x8 ra, rb;
+    float fra[8], frb[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float2 t2 = cs[c0 + i];
       const float fa = (float)a[i], fb = (float)b[i];
-      ra[i] = (bf16)(fa * t2.x - fb * t2.y);
-      rb[i] = (bf16)(fa * t2.y + fb * t2.x);
+      fra[i] = fa * t2.x - fb * t2.y;
+      frb[i] = fa * t2.y + fb * t2.x;
+    }
+    const int64_t kslot = (((int64_t)page * kv.n_kv_heads + (head - n_q_heads)) * kv.page_size + slot) * dh;
+    if (head >= n_q_heads && kv.fp8) {
+      // 8-bit cache: the rotated key goes from fp32 straight to its code (one rounding)
+      uint2 ca = make_uint2(0u, 0u), cb = make_uint2(0u, 0u);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ca.x |= f32_to_e4m3(fra[i] / kv.k_scale) << (8 * i);
+        ca.y |= f32_to_e4m3(fra[4 + i] / kv.k_scale) << (8 * i);
+        cb.x |= f32_to_e4m3(frb[i] / kv.k_scale) << (8 * i);
+        cb.y |= f32_to_e4m3(frb[4 + i] / kv.k_scale) << (8 * i);
+      }
+      uint8_t* dst = (uint8_t*)kv.k_pool + kslot;
+      *reinterpret_cast<uint2*>(dst + c0) = ca;
+      *reinterpret_cast<uint2*>(dst + half + c0) = cb;
+      continue;
+    }
+    bf16x8 ra, rb;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      ra[i] = (bf16)fra[i];
+      rb[i] = (bf16)frb[i];
     }
     if (head < n_q_heads) {
       st_bf16x8(hp + c0, ra);
       st_bf16x8(hp + half + c0, rb);
     } else {
-      const int kvh = head - n_q_heads;
-      bf16* dst = kpool + (((int64_t)page * kv.n_kv_heads + kvh) * kv.page_size + slot) * dh;
+      bf16* dst = kpool + kslot;
       st_bf16x8(dst + c0, ra);
       st_bf16x8(dst + half + c0, rb);
     }
@@ -146,7 +167,11 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(bf16* __restrict__ qkv, in
   const bf16* vrow = row + (int64_t)(n_q_heads + kv.n_kv_heads) * dh;
   for (int w = threadIdx.x; w < kv.n_kv_heads * dh; w += 256) {
     const int kvh = w / dh, c = w % dh;
-    vpool[(((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot] = vrow[w];
+    const int64_t vi = (((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot;
+    if (kv.fp8)
+      ((uint8_t*)kv.v_pool)[vi] = (uint8_t)f32_to_e4m3((float)vrow[w] / kv.v_scale);
+    else
+      vpool[vi] = vrow[w];
   }
 }
 
@@ -180,7 +205,18 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(int to_pages, bf16* __rest
     const int64_t ki = (((int64_t)page * kv.n_kv_heads + kvh) * kv.page_size + slot) * dh + c;
     const int64_t vi = (((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot;
     const int64_t pi = (int64_t)t * kv.n_kv_heads * dh + w;
-    if (to_pages) {
+    if (kv.fp8) {
+      // packed side stays bf16: import encodes value / scale, export gives code value * scale
+      uint8_t* k8 = (uint8_t*)kv.k_pool;
+      uint8_t* v8 = (uint8_t*)kv.v_pool;
+      if (to_pages) {
+        k8[ki] = (uint8_t)f32_to_e4m3((float)k_packed[pi] / kv.k_scale);
+        v8[vi] = (uint8_t)f32_to_e4m3((float)v_packed[pi] / kv.v_scale);
+      } else {
+        k_packed[pi] = (bf16)(e4m3_to_f32(k8[ki]) * kv.k_scale);
+        v_packed[pi] = (bf16)(e4m3_to_f32(v8[vi]) * kv.v_scale);
+      }
+    } else if (to_pages) {
       kpool[ki] = k_packed[pi];
       vpool[vi] = v_packed[pi];
     } else {
@@ -188,6 +224,35 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(int to_pages, bf16* __rest
       v_packed[pi] = vpool[vi];
     }
   }
+}
+
+// ------------------------------------------------------------------ E4M3 conversion (diagnostic)
+__global__ void e4m3_encode_kernel(const float* __restrict__ src, uint8_t* __restrict__ dst, int64_t n, float scale) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = (uint8_t)f32_to_e4m3(src[i] / scale);
+}
+// decodes four codes per thread with the conversion the attention kernel uses; n is rounded up to
+// a multiple of four by the caller's buffers
+__global__ void e4m3_decode_kernel(const uint32_t* __restrict__ src, float* __restrict__ dst, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  uint32_t lo, hi;
+  e4m3x4_to_bf16x4(src[i], lo, hi);
+  float4 o;
+  o.x = __uint_as_float(lo << 16);
+  o.y = __uint_as_float(lo & 0xffff0000u);
+  o.z = __uint_as_float(hi << 16);
+  o.w = __uint_as_float(hi & 0xffff0000u);
+  reinterpret_cast<float4*>(dst)[i] = o;
+}
+
+hipError_t launch_e4m3_convert(int to_codes, const void* src, void* dst, int64_t n, float scale, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  if (to_codes)
+    e4m3_encode_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>((const float*)src, (uint8_t*)dst, n, scale);
+  else
+    e4m3_decode_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, s>>>((const uint32_t*)src, (float*)dst, n / 4);
+  return hipGetLastError();
 }
 
 hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const KvLayout& kv,

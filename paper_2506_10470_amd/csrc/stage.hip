@@ -43,8 +43,10 @@ struct tdp_stage {
   float *g_attn = nullptr, *g_mlp = nullptr;
   float* bqkv = nullptr;  // [L][Nqkv_pad]: q / k / v projection biases, zero until set
   bool has_bias = false;
-  uint16_t *kpool = nullptr, *vpool = nullptr;
+  uint8_t *kpool = nullptr, *vpool = nullptr;
   int64_t pool_elems = 0;  // per layer, per pool
+  int64_t pool_bytes = 0;  // pool_elems * (2: bf16 | 1: E4M3 codes)
+  float k_scale = 1.f, v_scale = 1.f;
   uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *u = nullptr;  // bf16 activations
   float *h = nullptr, *xa = nullptr, *xb = nullptr;  // residual stream, fp32 between layers
   float* ws = nullptr;
@@ -84,6 +86,13 @@ int check_config(const tdp_stage_config* c) {
     return fail(TDP_EINVAL, "max_seqs must be >= 1 when max_tokens > 0");
   if (c->max_pages_per_seq < 1) return fail(TDP_EINVAL, "max_pages_per_seq must be >= 1");
   if ((int64_t)c->max_pages_per_seq * 16 > (1 << 20)) return fail(TDP_EINVAL, "max_pages_per_seq too large");
+  if (c->kv_dtype != TDP_KV_BF16 && c->kv_dtype != TDP_KV_FP8_E4M3)
+    return fail(TDP_EINVAL, "kv_dtype must be TDP_KV_BF16 or TDP_KV_FP8_E4M3");
+  if (c->kv_dtype == TDP_KV_FP8_E4M3) {
+    // 0 means 1; otherwise a finite positive number
+    if (!(c->k_scale >= 0.f) || !(c->v_scale >= 0.f) || !(c->k_scale < 1e30f) || !(c->v_scale < 1e30f))
+      return fail(TDP_EINVAL, "k_scale / v_scale must be finite and >= 0 (0 = 1)");
+  }
   return TDP_OK;
 }
 
@@ -123,8 +132,11 @@ struct Timer {
 
 KvLayout kv_layout(tdp_stage* st, int layer) {
   KvLayout kv;
-  kv.k_pool = st->kpool + (int64_t)layer * st->pool_elems;
-  kv.v_pool = st->vpool + (int64_t)layer * st->pool_elems;
+  kv.k_pool = st->kpool + (int64_t)layer * st->pool_bytes;
+  kv.v_pool = st->vpool + (int64_t)layer * st->pool_bytes;
+  kv.fp8 = st->cfg.kv_dtype == TDP_KV_FP8_E4M3;
+  kv.k_scale = st->k_scale;
+  kv.v_scale = st->v_scale;
   kv.num_pages = st->cfg.num_pages;
   kv.n_kv_heads = st->cfg.n_kv_heads;
   kv.head_dim = st->cfg.head_dim;
@@ -225,7 +237,7 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
 
 extern "C" {
 
-int tdp_abi_version(void) { return 1; }
+int tdp_abi_version(void) { return 2; }
 
 const char* tdp_last_error(void) { return g_err.c_str(); }
 
@@ -246,6 +258,11 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
   st->Ngu_pad = 2 * st->Fpad;
   st->maxM = c.max_batch > c.max_tokens ? c.max_batch : c.max_tokens;
   st->pool_elems = (int64_t)c.num_pages * c.n_kv_heads * 16 * dh;
+  st->pool_bytes = st->pool_elems * (c.kv_dtype == TDP_KV_FP8_E4M3 ? 1 : 2);
+  if (c.kv_dtype == TDP_KV_FP8_E4M3) {
+    st->k_scale = c.k_scale > 0.f ? c.k_scale : 1.f;
+    st->v_scale = c.v_scale > 0.f ? c.v_scale : 1.f;
+  }
   st->max_pos = c.max_pages_per_seq * 16;
   st->max_chunks = (st->max_pos + kDecodeSpanMin - 1) / kDecodeSpanMin;
 
@@ -260,8 +277,8 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
   A(&st->g_attn, L * d, true);
   A(&st->g_mlp, L * d, true);
   A(&st->bqkv, L * st->Nqkv_pad, true);
-  A(&st->kpool, L * st->pool_elems, true);
-  A(&st->vpool, L * st->pool_elems, true);
+  A(&st->kpool, L * st->pool_bytes, true);
+  A(&st->vpool, L * st->pool_bytes, true);
   const int64_t M = (st->maxM + 1) & ~1;  // row pairs: pair-interleaved activation buffers
   A(&st->y, M * d, true);
   A(&st->qkv, M * st->Nqkv_pad, true);
@@ -398,9 +415,9 @@ int tdp_stage_set_weight(tdp_stage* st, int32_t layer, int32_t which, const void
 int tdp_stage_kv_pool(tdp_stage* st, int32_t layer, void** k_dev, void** v_dev, int64_t* bytes) {
   if (!st) return fail(TDP_EINVAL, "null stage");
   if (layer < 0 || layer >= st->cfg.n_layers) return fail(TDP_EINVAL, "layer out of range");
-  if (k_dev) *k_dev = st->kpool + (int64_t)layer * st->pool_elems;
-  if (v_dev) *v_dev = st->vpool + (int64_t)layer * st->pool_elems;
-  if (bytes) *bytes = st->pool_elems * 2;
+  if (k_dev) *k_dev = st->kpool + (int64_t)layer * st->pool_bytes;
+  if (v_dev) *v_dev = st->vpool + (int64_t)layer * st->pool_bytes;
+  if (bytes) *bytes = st->pool_bytes;
   return TDP_OK;
 }
 
@@ -486,6 +503,24 @@ int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out,
   if (wt) (void)hipFree(wt);
   if (ws) (void)hipFree(ws);
   if (e != hipSuccess) return fail_hip(e, "tdp_gemm_bf16");
+  return TDP_OK;
+}
+
+int tdp_e4m3_from_f32(const float* src, uint8_t* codes, int64_t n, float scale, void* stream) {
+  if (n < 0) return fail(TDP_EINVAL, "negative size");
+  if (n == 0) return TDP_OK;
+  if (!src || !codes) return fail(TDP_EINVAL, "null pointer");
+  if (!(scale > 0.f) || !(scale < 1e30f)) return fail(TDP_EINVAL, "scale must be finite and > 0");
+  HIP_TRY(launch_e4m3_convert(1, src, codes, n, scale, (hipStream_t)stream));
+  return TDP_OK;
+}
+
+int tdp_e4m3_to_f32(const uint8_t* codes, float* dst, int64_t n, void* stream) {
+  if (n < 0 || n % 4) return fail(TDP_EINVAL, "n must be a non-negative multiple of 4");
+  if (n == 0) return TDP_OK;
+  if (!codes || !dst) return fail(TDP_EINVAL, "null pointer");
+  if (((uintptr_t)codes & 3) || ((uintptr_t)dst & 15)) return fail(TDP_EINVAL, "codes must be 4-byte and dst 16-byte aligned");
+  HIP_TRY(launch_e4m3_convert(0, codes, dst, n, 1.f, (hipStream_t)stream));
   return TDP_OK;
 }
 

@@ -45,6 +45,52 @@ __device__ __forceinline__ int64_t operand_offset(const L& lay, int r, int k) {
   return (int64_t)(r >> 1) * lay.pair + (int64_t)(k >> 5) * lay.kb + (int64_t)(r & 1) * lay.par + (k & 31);
 }
 
+// ---- 8-bit KV cache: OCP E4M3 (sign, 4 exponent bits with bias 7, 3 mantissa bits; exponent field
+// 0 is subnormal, no infinities, S.1111.111 is NaN, largest finite magnitude 448) -------------------
+// fp32 -> code: round to nearest, ties to the even code; magnitudes from 448 up (infinity included)
+// saturate to +-448; NaN -> 0x7f | sign.  Integer arithmetic only, so the result does not depend on
+// any conversion mode of the hardware.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float x) {
+  const uint32_t u = __float_as_uint(x);
+  const uint32_t sign = (u >> 24) & 0x80u;
+  const uint32_t a = u & 0x7fffffffu;
+  if (a > 0x7f800000u) return sign | 0x7fu;
+  if (a >= 0x43e00000u) return sign | 0x7eu;                  // |x| >= 448
+  if (a < 0x3c800000u)                                        // |x| < 2^-6: multiples of 2^-9
+    return sign | (uint32_t)__float2int_rn(__uint_as_float(a) * 512.0f);  // 8 is the code of 2^-6 itself
+  const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u);         // nearest even at mantissa bit 20
+  return sign | ((r >> 20) - (120u << 3));                    // exponent bias 127 -> 7
+}
+// code -> fp32, exact (not used on the hot path, which converts with the hardware instruction)
+__device__ __forceinline__ float e4m3_to_f32(uint32_t c) {
+  const uint32_t sign = (c & 0x80u) << 24, e = (c >> 3) & 15u, m = c & 7u;
+  if (e == 15u && m == 7u) return __uint_as_float(sign | 0x7fc00000u);
+  if (e == 0u) return __uint_as_float(sign | __float_as_uint((float)m * 0.001953125f));
+  return __uint_as_float(sign | ((e + 120u) << 23) | (m << 20));
+}
+// Four codes (one dword, lowest byte first) -> four bf16 as two dwords.  v_cvt_pk_f32_fp8 decodes
+// E4M3 on gfx950; every E4M3 value is a bf16 value, so keeping the upper halves is exact.
+__device__ __forceinline__ void e4m3x4_to_bf16x4(uint32_t w, uint32_t& lo, uint32_t& hi) {
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+  const f32x2_t b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+  lo = __builtin_amdgcn_perm(__float_as_uint(a.y), __float_as_uint(a.x), 0x07060302u);
+  hi = __builtin_amdgcn_perm(__float_as_uint(b.y), __float_as_uint(b.x), 0x07060302u);
+}
+// 16 codes -> the two MFMA operands they make (codes 0..7 and 8..15)
+__device__ __forceinline__ void e4m3x16_to_bf16x8x2(uint4 raw, bf16x8& first, bf16x8& second) {
+  union {
+    uint32_t u[4];
+    bf16x8 v;
+  } f, g;
+  e4m3x4_to_bf16x4(raw.x, f.u[0], f.u[1]);
+  e4m3x4_to_bf16x4(raw.y, f.u[2], f.u[3]);
+  e4m3x4_to_bf16x4(raw.z, g.u[0], g.u[1]);
+  e4m3x4_to_bf16x4(raw.w, g.u[2], g.u[3]);
+  first = f.v;
+  second = g.v;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

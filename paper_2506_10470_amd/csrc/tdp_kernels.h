@@ -73,9 +73,11 @@ hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float*
 
 // ---- RoPE + KV append ------------------------------------------------------------------------
 struct KvLayout {
-  void* k_pool;   // bf16 [num_pages][Hkv][page][dh]
-  void* v_pool;   // bf16 [num_pages][Hkv][dh][page]   (token index fastest)
+  void* k_pool;   // [num_pages][Hkv][page][dh]
+  void* v_pool;   // [num_pages][Hkv][dh][page]   (token index fastest)
   int num_pages, n_kv_heads, head_dim, page_size;
+  int fp8;        // 0: elements are bf16; 1: elements are E4M3 codes of value / scale (one byte each)
+  float k_scale, v_scale;
 };
 // decode: token b sits at position ctx_lens[b] of sequence b.  prefill: token t of sequence s
 // (cu_seqlens[s] <= t < cu_seqlens[s+1]) sits at position t - cu_seqlens[s].
@@ -103,6 +105,9 @@ hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_he
                               const int32_t* ctx_lens, const int4* items, const int32_t* item_pages, float* part_o,
                               float* part_ml, int max_spans, int span_len, void* out, OperandLayout out_layout,
                               hipStream_t s);
+// diagnostic: dst[i] = E4M3 code of src[i] / scale (to_codes) or dst[i] = value of code src[i] (fp32), through the
+// same device functions the KV kernels use (the decode direction through the hardware conversion)
+hipError_t launch_e4m3_convert(int to_codes, const void* src, void* dst, int64_t n, float scale, hipStream_t s);
 hipError_t launch_attn_prefill(const void* qkv, int64_t ld, int total_tokens, int n_seqs, int n_q_heads,
                                const KvLayout& kv, const int32_t* cu_seqlens, const int32_t* block_tables,
                                int max_pages_per_seq, void* out, OperandLayout out_layout, hipStream_t s);

@@ -17,6 +17,7 @@ WEIGHT_IDS = {"wq": WQ, "wk": WK, "wv": WV, "wo": WO, "wg": WG, "wu": WU, "wd": 
               "g_attn": G_ATTN, "g_mlp": G_MLP, "bq": BQ, "bk": BK, "bv": BV}
 F32, BF16 = 0, 1
 HOST, DEVICE = 0, 1
+KV_BF16, KV_FP8_E4M3 = 0, 1
 TIMING_CLASSES = ("rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gate_up", "gemm_down")
 
 
@@ -25,7 +26,8 @@ class StageConfig(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ff", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("page_size", C.c_int32),
                 ("num_pages", C.c_int32), ("max_batch", C.c_int32), ("max_tokens", C.c_int32),
-                ("max_seqs", C.c_int32), ("max_pages_per_seq", C.c_int32)]
+                ("max_seqs", C.c_int32), ("max_pages_per_seq", C.c_int32),
+                ("kv_dtype", C.c_int32), ("k_scale", C.c_float), ("v_scale", C.c_float)]
 
 
 class EndsConfig(C.Structure):
@@ -65,6 +67,8 @@ _SIGS = {
     "tdp_stage_decode": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "tdp_stage_set_layer_range": (C.c_int, [_vp, _i32, _i32]),
     "tdp_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "tdp_e4m3_from_f32": (C.c_int, [_vp, _vp, _i64, C.c_float, _vp]),
+    "tdp_e4m3_to_f32": (C.c_int, [_vp, _vp, _i64, _vp]),
     "tdp_stage_timing_enable": (C.c_int, [_vp, _i32]),
     "tdp_stage_timing_read": (C.c_int, [_vp, C.POINTER(C.c_float)]),
     "tdp_ends_create": (C.c_int, [C.POINTER(EndsConfig), C.POINTER(_vp)]),
@@ -160,6 +164,14 @@ def tdp_stage_set_layer_range(st, first: int, count: int) -> None:
 def tdp_gemm_bf16(A, W, residual, out, M, N, K, epilogue=0, tile=0, splits=0, stream=None) -> None:
     _check(lib.tdp_gemm_bf16(_ptr(A), _ptr(W), _ptr(residual), _ptr(out), M, N, K, epilogue, tile, splits,
                              _stream(stream)))
+
+
+def tdp_e4m3_from_f32(src, codes, n, scale=1.0, stream=None) -> None:
+    _check(lib.tdp_e4m3_from_f32(_ptr(src), _ptr(codes), n, scale, _stream(stream)))
+
+
+def tdp_e4m3_to_f32(codes, dst, n, stream=None) -> None:
+    _check(lib.tdp_e4m3_to_f32(_ptr(codes), _ptr(dst), n, _stream(stream)))
 
 
 def tdp_stage_timing_enable(st, on: bool) -> None:

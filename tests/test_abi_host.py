@@ -25,14 +25,15 @@ def test_every_declared_symbol_is_exported():
     for name in declared:
         assert hasattr(tdp.lib, name), name
         assert name in tdp._SIGS, "binding lacks " + name
-    assert tdp.tdp_abi_version() == 1
+    assert tdp.tdp_abi_version() == 2
 
 
 @pytest.mark.parametrize("bad", [
     dict(n_layers=0), dict(d_model=100), dict(head_dim=96), dict(n_q_heads=6, n_kv_heads=4),
     dict(n_q_heads=34, n_kv_heads=2), dict(d_ff=0), dict(d_ff=690), dict(page_size=32), dict(num_pages=0),
     dict(max_batch=0, max_tokens=0), dict(max_batch=-1), dict(max_pages_per_seq=0), dict(rope_base=0.0),
-    dict(max_tokens=8, max_seqs=0),
+    dict(max_tokens=8, max_seqs=0), dict(kv_dtype=2), dict(kv_dtype=-1),
+    dict(kv_dtype=1, k_scale=-1.0), dict(kv_dtype=1, v_scale=float("inf")), dict(kv_dtype=1, k_scale=float("nan")),
 ])
 def test_create_rejects_bad_config_before_any_gpu_work(bad):
     with pytest.raises(tdp.TdpError) as e:
@@ -52,6 +53,16 @@ def test_null_arguments_are_einval():
     assert tdp.lib.tdp_stage_set_weight(None, 0, 0, None, 0, 0, 1, 1) == tdp.EINVAL
     assert tdp.lib.tdp_stage_timing_read(None, None) == tdp.EINVAL
     tdp.lib.tdp_stage_destroy(None)          # allowed
+
+
+def test_e4m3_diagnostics_reject_bad_arguments():
+    assert tdp.lib.tdp_e4m3_from_f32(None, None, 4, 1.0, None) == tdp.EINVAL
+    assert tdp.lib.tdp_e4m3_from_f32(16, 16, -1, 1.0, None) == tdp.EINVAL
+    assert tdp.lib.tdp_e4m3_from_f32(16, 16, 4, 0.0, None) == tdp.EINVAL
+    assert tdp.lib.tdp_e4m3_to_f32(None, None, 4, None) == tdp.EINVAL
+    assert tdp.lib.tdp_e4m3_to_f32(16, 16, 6, None) == tdp.EINVAL          # not a multiple of 4
+    assert tdp.lib.tdp_e4m3_to_f32(18, 16, 4, None) == tdp.EINVAL          # misaligned codes
+    assert tdp.lib.tdp_e4m3_from_f32(None, None, 0, 1.0, None) == tdp.OK   # empty: nothing to do
 
 
 def test_gemm_entry_rejects_bad_shapes():

@@ -110,18 +110,30 @@ def rand_layer(d, sh, f, rng):
                           m(f, d), 1 + rng.normal(0, 0.1, d), 1 + rng.normal(0, 0.1, d))
 
 
-def test_cache_holds_representable_values_and_prefill_attention_does_not_see_them():
+def by_hand_layer(x, k_all, v_all, p0, w, sh):
+    """The layer recomposed from the oracle's primitives with the attention inputs given."""
+    L = x.shape[0]
+    y = O.rmsnorm(x, w.g_attn, sh.rms_eps)
+    q = O.rope((y @ w.wq).reshape(L, sh.n_q_heads, sh.head_dim), np.arange(p0, p0 + L), sh.rope_base)
+    h = x + O.attention(q, k_all, v_all, p0, sh) @ w.wo
+    y2 = O.rmsnorm(h, w.g_mlp, sh.rms_eps)
+    return h + (O.silu(y2 @ w.wg) * (y2 @ w.wu)) @ w.wd
+
+
+def test_cache_holds_representable_values_and_attention_reads_the_cache():
     rng = np.random.default_rng(5)
     w = rand_layer(16, SH, 24, rng)
     x = rng.normal(size=(7, 16))
     q8 = O.Shape(4, 2, 8, kv_scales=(0.5, 2.0))
     out_plain, k_plain, v_plain = O.layer_forward(x, O.empty_cache(SH), O.empty_cache(SH), w, SH)
     out_q8, k8, v8 = O.layer_forward(x, O.empty_cache(SH), O.empty_cache(SH), w, q8)
-    assert np.array_equal(out_q8, out_plain)                  # prefill computes with the values as they are
     assert np.array_equal(k8, F8.kv_roundtrip(k_plain, 0.5)) and np.array_equal(v8, F8.kv_roundtrip(v_plain, 2.0))
     assert not np.array_equal(k8, k_plain)
     grid = set((F8.e4m3_decode_table()[:0x7F] * 0.5).tolist())
     assert all(abs(v) in grid for v in k8.ravel())
+    # prefill attends to the stored keys and values, not to the ones it computed
+    assert np.allclose(out_q8, by_hand_layer(x, k8, v8, 0, w, SH), atol=1e-12)
+    assert np.max(np.abs(out_q8 - out_plain)) > 1e-6
 
 
 def test_decode_step_attends_to_the_stored_token_and_stored_context():
@@ -131,20 +143,13 @@ def test_decode_step_attends_to_the_stored_token_and_stored_context():
     kc, vc = rng.normal(size=(5, 2, 8)), rng.normal(size=(5, 2, 8))
     kc8, vc8 = F8.kv_roundtrip(kc, 1.0), F8.kv_roundtrip(vc, 1.0)
     x = rng.normal(size=(1, 16))
-    out, k_all, v_all = O.layer_forward(x, kc8, vc8, w, q8, attend_stored=True)
-    # the same step through the plain layer with the attention inputs replaced by hand
-    _, k_plain, v_plain = O.layer_forward(x, kc8, vc8, w, SH)
+    out, k_all, v_all = O.layer_forward(x, kc8, vc8, w, q8)
+    out_plain, k_plain, v_plain = O.layer_forward(x, kc8, vc8, w, SH)
     assert np.array_equal(k_all[:5], kc8) and np.array_equal(k_all[5:], F8.kv_roundtrip(k_plain[5:], 1.0))
-    y = O.rmsnorm(x, w.g_attn, SH.rms_eps)
-    q = O.rope((y @ w.wq).reshape(1, 4, 8), np.array([5]), SH.rope_base)
-    a = O.attention(q, k_all, v_all, 5, SH)
-    h = x + a @ w.wo
-    y2 = O.rmsnorm(h, w.g_mlp, SH.rms_eps)
-    want = h + (O.silu(y2 @ w.wg) * (y2 @ w.wu)) @ w.wd
-    assert np.allclose(out, want, atol=1e-12)
+    assert np.array_equal(v_all[5:], F8.kv_roundtrip(v_plain[5:], 1.0))
+    assert np.allclose(out, by_hand_layer(x, k_all, v_all, 5, w, SH), atol=1e-12)
     # and it differs from attending to the unrounded new token
-    out_unstored, _, _ = O.layer_forward(x, kc8, vc8, w, q8, attend_stored=False)
-    assert np.max(np.abs(out_unstored - out)) > 1e-6
+    assert np.max(np.abs(out_plain - out)) > 1e-6
 
 
 def test_representable_cache_makes_the_option_a_no_op():
@@ -160,22 +165,25 @@ def test_representable_cache_makes_the_option_a_no_op():
     shq = O.Shape(2, 1, 4, rms_eps=0.0, kv_scales=(1.0, 1.0))
     shp = O.Shape(2, 1, 4, rms_eps=0.0)
     # position 0: the rotation is the identity, so k = v = +-1 exactly
-    a, ka, va = O.layer_forward(x, O.empty_cache(sh), O.empty_cache(sh), w, shq, attend_stored=True)
+    a, ka, va = O.layer_forward(x, O.empty_cache(sh), O.empty_cache(sh), w, shq)
     b, kb, vb = O.layer_forward(x, O.empty_cache(sh), O.empty_cache(sh), w, shp)
     assert np.array_equal(ka, kb) and np.array_equal(va, vb) and np.array_equal(a, b)
 
 
-def test_stage_decode_uses_the_stored_version_and_stage_prefill_does_not():
+def test_stage_prefill_and_decode_carry_the_stored_cache():
     rng = np.random.default_rng(9)
     layers = [rand_layer(16, SH, 24, rng) for _ in range(2)]
     q8 = O.Shape(4, 2, 8, kv_scales=(1.0, 1.0))
     prompts = [rng.normal(size=(6, 16)), rng.normal(size=(3, 16))]
     outs8, caches8 = O.stage_prefill(prompts, layers, q8)
     outs, caches = O.stage_prefill(prompts, layers, SH)
-    assert all(np.array_equal(a, b) for a, b in zip(outs8, outs))
-    assert np.array_equal(caches8[0][1][0], F8.kv_roundtrip(caches[0][1][0], 1.0))
+    # layer 0 sees the same input either way: its cache is the plain one through the format
+    assert np.array_equal(caches8[0][0][0], F8.kv_roundtrip(caches[0][0][0], 1.0))
+    assert np.max(np.abs(outs8[0] - outs[0])) > 1e-6
     xs = [rng.normal(size=16), rng.normal(size=16)]
     step8, new8 = O.stage_decode(xs, caches8, layers, q8)
-    want0, _ = O.stage_forward(xs[0][None, :], caches8[0], layers, q8, attend_stored=True)
+    want0, _ = O.stage_forward(xs[0][None, :], caches8[0], layers, q8)
     assert np.array_equal(step8[0], want0[0])
     assert new8[1][0][0].shape[0] == 4
+    grid = set(F8.e4m3_decode_table()[:0x7F].tolist())
+    assert all(abs(v) in grid for v in new8[1][1][1].ravel())
