@@ -33,7 +33,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32):
+def build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32, kv_scales=None):
     """One stage sized for the decode batch and the prefill batch, page ranges disjoint."""
     import torch
     max_pps = 4096 // 16 + 2
@@ -42,7 +42,7 @@ def build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32):
     pre_tables = np.where(pre.tables >= 0, pre.tables + dec.num_pages, -1).astype(np.int32)
     t0 = time.time()
     st = Stage(tdp, shape, dec.num_pages + pre.num_pages, len(dec_ctx), int(pre_lens.sum()), len(pre_lens),
-               max_pps, load_weights=True)
+               max_pps, load_weights=True, kv_scales=kv_scales)
     torch.cuda.synchronize()
     log("stage created, weights loaded: %.1f s" % (time.time() - t0))
     # pre-existing KV ~ N(0,1), written through the library's import kernel
@@ -196,6 +196,37 @@ def cpu_baseline(shape, dec_ctx, cu, budget_layers=4, n_requests=64):
                           float(np.mean([dec_ctx[b] for b in sample])), budget_layers, shape.n_layers, dt, t_prep)}
 
 
+def fp8_kv_section(tdp, W, Stage, A, shape, sargs, dec_ctx, i32, steps, warmup):
+    """The same decode step with the KV cache held as 8-bit E4M3 codes (scales 1): the cache bytes
+    the step must read are halved, everything else is unchanged.  An option of the library, not the
+    headline configuration (the paper keeps the cache in the model's 16-bit type)."""
+    import torch
+    B = len(dec_ctx)
+    st, dec, _, _, _ = build_stage(tdp, W, Stage, shape, dec_ctx, np.array([16], dtype=np.int64), i32,
+                                   kv_scales=(1.0, 1.0))
+    stream = torch.cuda.current_stream()
+    x = W.hidden_states(shape, B, 1, device="cuda")
+    out = torch.empty_like(x)
+    ctx_d, tab_d = i32(dec.ctx_lens), i32(dec.tables)
+    fn = lambda b=B: tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, b, out, stream)
+    ms = time_calls(fn, warmup, steps)
+    work = A.decode_step_work(*sargs, dec_ctx, kv_elem_bytes=1)
+    ct = class_times(tdp, st, fn, 5)
+    kern = kernel_rooflines(shape, B, work["kv_read_bytes"], work["attn_flops"], ct, "decode")
+    sweep = []
+    for b in (64, 128, 256):
+        if b >= B:
+            continue
+        msb = time_calls(lambda: fn(b), 3, 10)
+        sweep.append({"batch": b, "ms_per_step": round(msb, 4), "tok_s": round(b / msb * 1e3, 1)})
+    st.close()
+    torch.cuda.empty_cache()
+    return {"kv_dtype": "e4m3", "k_scale": 1.0, "v_scale": 1.0, "batch": B, "ms_per_step": round(ms, 4),
+            "tok_s": round(B / ms * 1e3, 1), "alg_bytes_per_step": work["bytes"],
+            "hbm_gbs": round(work["bytes"] / ms / 1e6, 1), "class_ms": {k: round(v, 4) for k, v in ct.items()},
+            "attention": kern.get("attention"), "sweep": sweep}
+
+
 def ends_section(tdp, W, shape, batch, i32, vocab=32000):
     """What the first and the last stage of a pipeline add per decode step: the token-embedding
     lookup, and final RMSNorm + vocabulary projection (fp32 logits) + greedy selection."""
@@ -266,6 +297,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--kv-fp8", action="store_true",
+                    help="run the 8-bit KV-cache section even in the lean (--no-sweep) mode")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size kernel that rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -413,6 +446,11 @@ def main():
 
     st.close()
     torch.cuda.empty_cache()
+    if args.kv_fp8 or not (args.layers or args.no_sweep):
+        result["decode_fp8_kv"] = fp8_kv_section(tdp, W, Stage, A, shape, sargs, dec_ctx, i32, args.steps, args.warmup)
+        log("decode B=%d with an 8-bit KV cache: %.3f ms/step, %.0f tok/s (attention %.3f ms per step)" % (
+            B, result["decode_fp8_kv"]["ms_per_step"], result["decode_fp8_kv"]["tok_s"],
+            result["decode_fp8_kv"]["class_ms"]["attention"]))
     if not args.layers and not args.no_sweep:
         result["ends"] = ends_section(tdp, W, shape, B, i32)
         log("pipeline ends at batch %d: embedding %.3f ms, final norm + vocabulary projection + greedy %.3f ms" % (

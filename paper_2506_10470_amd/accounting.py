@@ -22,14 +22,16 @@ def kv_bytes_per_token(n_layers: int, n_kv_heads: int, head_dim: int, elem_bytes
 
 
 def decode_step_work(n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff,
-                     ctx_lens: Sequence[int], elem_bytes: int = 2):
+                     ctx_lens: Sequence[int], elem_bytes: int = 2, kv_elem_bytes: int = 0):
     """Algorithmic (bytes, flops) of one decode step.  ctx_lens = tokens already
     cached per request; the step reads ctx+1 tokens of K/V and appends one.
     Weights are read once per step whatever the batch size; activations between
-    kernels are implementation traffic and are not counted."""
+    kernels are implementation traffic and are not counted.  kv_elem_bytes: bytes
+    per cached element when the cache is held in another type than the model
+    (0 = the same)."""
     B = len(ctx_lens)
     P = matmul_params_per_layer(d_model, n_q_heads, n_kv_heads, head_dim, d_ff)
-    kvtok = kv_bytes_per_token(1, n_kv_heads, head_dim, elem_bytes)
+    kvtok = kv_bytes_per_token(1, n_kv_heads, head_dim, kv_elem_bytes or elem_bytes)
     span = sum(int(c) + 1 for c in ctx_lens)
     w_bytes = n_layers * P * elem_bytes
     kv_read = n_layers * kvtok * span

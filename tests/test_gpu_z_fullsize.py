@@ -194,3 +194,49 @@ def test_70b_quarter_stage_decode_512_and_prefill_16_prompts(tdp):
 def test_qwen32b_quarter_stage_decode_256_and_prefill(tdp):
     """The paper's third model (Table 2): GQA group of 5, q/k/v biases, rope base 1e6, eps 1e-6."""
     run_full_size(tdp, "qwen32b_quarter", [256], 16, n_prefill_samples=1)
+
+
+def test_70b_decode_512_with_an_8_bit_cache(tdp):
+    """The 8-bit KV-cache option in the launch configuration the benchmark times it in: the headline
+    batch (512 requests, contexts up to 4096, one 4096-token span per workgroup), two 70B-shaped
+    layers.  The cache is imported, so its codes are the oracle's bit for bit and the sampled
+    requests (shortest, median and longest context) are held to the plain tolerance."""
+    from oracle import fp8_oracle as F8
+    config, scales, B = "70b_quarter", (1.0, 1.0), 512
+    sh = W.SHAPES[config].with_layers(2)
+    osh = oracle_shape(sh)
+    osh.kv_scales = scales
+    ctx = W.decode_ctx_lens(config, B)
+    dec = W.make_decode_batch(ctx, max_pages_per_seq=MAX_PPS)
+    total = int(ctx.sum())
+    cu = np.zeros(B + 1, dtype=np.int64)
+    cu[1:] = np.cumsum(ctx)
+    with Stage(tdp, sh, dec.num_pages, B, 0, 0, MAX_PPS, kv_scales=scales) as st:
+        tab_d, ctx_d = i32(dec.tables), i32(dec.ctx_lens)
+        for l in range(sh.n_layers):
+            k = W.kv_packed(sh, l, "k", total, 1, device="cuda")
+            v = W.kv_packed(sh, l, "v", total, 1, device="cuda")
+            tdp.tdp_stage_kv_import(st.h, l, k, v, i32(cu), tab_d, B, total)
+            torch.cuda.synchronize()
+            del k, v
+        x = W.hidden_states(sh, B, 1, device="cuda")
+        out = torch.full((B, sh.d_model), float("nan"), dtype=torch.bfloat16, device="cuda")
+        tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, B, out)
+        torch.cuda.synchronize()
+        got = f64(out)
+        assert np.isfinite(got).all()
+        order = np.argsort(ctx, kind="stable")
+        samples = sorted({int(order[0]), int(order[B // 2]), int(order[-1])})
+        states = {i: f64(x[i:i + 1]) for i in samples}
+        for l in range(sh.n_layers):
+            w = oracle_layer(sh, l)
+            for i in samples:
+                kc = f64(W.kv_packed(sh, l, "k", total, 1, device="cuda", tok0=int(cu[i]), toks=int(ctx[i])))
+                vc = f64(W.kv_packed(sh, l, "v", total, 1, device="cuda", tok0=int(cu[i]), toks=int(ctx[i])))
+                states[i], _, _ = O.layer_forward(states[i], F8.kv_roundtrip(kc, scales[0]),
+                                                  F8.kv_roundtrip(vc, scales[1]), w, osh)
+            del w
+        for i in samples:
+            e = row_rel_err(got[i:i + 1], states[i])
+            say("[%s, 8-bit cache] decode batch %d request %d (ctx %d): err %.2e" % (config, B, i, int(ctx[i]), e))
+            assert e <= TOL, (i, e)
