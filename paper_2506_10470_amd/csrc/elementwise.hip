@@ -265,11 +265,11 @@ hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const Kv
 }
 
 // ------------------------------------------------------------------ weight repack (one-time)
-// dst(row_of(n), k) = bf16(src[k][n]) through a 32x32 LDS transpose; dst is pair-interleaved
-// (rows 2p, 2p+1 alternate in 32-column blocks) with dst_ld columns.
+// dst(row_of(n), k) = bf16(src[k][n]) through a 32x32 LDS transpose; dst is in the weight layout
+// (layout_weights) with dst_ld columns.
 __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ src, int src_is_f32,
                                                      int64_t K, int64_t N, bf16* __restrict__ dst,
-                                                     int64_t dst_ld, int64_t row_off, int mode) {
+                                                     OperandLayout lay, int64_t row_off, int mode) {
   __shared__ float tile[32][33];
   const int64_t k0 = (int64_t)blockIdx.y * 32, n0 = (int64_t)blockIdx.x * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ sr
       int64_t row;
       if (mode == 0) row = row_off + n;
       else row = (n / 32) * 64 + (n % 32) + (mode == 2 ? 32 : 0);
-      dst[(row >> 1) * 2 * dst_ld + (k >> 5) * 64 + (row & 1) * 32 + (k & 31)] = (bf16)tile[tx][r];
+      dst[operand_offset(lay, (int)row, (int)k)] = (bf16)tile[tx][r];
     }
   }
 }
@@ -295,7 +295,8 @@ __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ sr
 hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in, int64_t cols_out, void* dst,
                          int64_t dst_ld, int64_t row_off, int mode, hipStream_t s) {
   dim3 grid((unsigned)((cols_out + 31) / 32), (unsigned)((rows_in + 31) / 32));
-  repack_kernel<<<grid, 256, 0, s>>>(src, src_is_f32, rows_in, cols_out, (bf16*)dst, dst_ld, row_off, mode);
+  repack_kernel<<<grid, 256, 0, s>>>(src, src_is_f32, rows_in, cols_out, (bf16*)dst, layout_weights(dst_ld), row_off,
+                                     mode);
   return hipGetLastError();
 }
 

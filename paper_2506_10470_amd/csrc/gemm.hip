@@ -236,17 +236,17 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_dma_ker
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);  // 16-byte chunk of the stage's k range
     int m = row;
     if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
-    a_goff[j] = (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + (c_sw >> 2) * p.a_lay.kb + (c_sw & 3) * 8);
+    a_goff[j] = (unsigned)(operand_row_offset(p.a_lay, m) + (c_sw >> 2) * p.a_lay.kb + (c_sw & 3) * 8);
   }
 #pragma unroll
   for (int j = 0; j < IPW; ++j) {
     const int row = (lw_id * IPW + j) * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
-    w_goff[j] = (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + (c_sw >> 2) * p.w_lay.kb + (c_sw & 3) * 8);
+    w_goff[j] = (unsigned)(operand_row_offset(p.w_lay, row) + (c_sw >> 2) * p.w_lay.kb + (c_sw & 3) * 8);
   }
   constexpr int KB_PER_STAGE = BK / 32;
-  const bf16* a_base = p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * KB_PER_STAGE * p.a_lay.kb;
-  const bf16* w_base = p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * KB_PER_STAGE * p.w_lay.kb;
+  const bf16* a_base = p.A + operand_row_offset(p.a_lay, m0) + (int64_t)kt_begin * KB_PER_STAGE * p.a_lay.kb;
+  const bf16* w_base = p.W + operand_row_offset(p.w_lay, n0) + (int64_t)kt_begin * KB_PER_STAGE * p.w_lay.kb;
   // t relative to kt_begin, clamped so the tail re-fetches the last stage (never read)
   auto dma_stage = [&](int t) {
     const int tc = t < n_stages ? t : n_stages - 1;
@@ -399,24 +399,23 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
     int m = row;
     if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
-    a_goff[j] = 2u * (unsigned)((m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + c_sw * 8) + (unsigned)(kImmBias - j * 1024);
+    a_goff[j] = 2u * (unsigned)(operand_row_offset(p.a_lay, m) + c_sw * 8) + (unsigned)(kImmBias - j * 1024);
   }
-  // weight rows need no clamp: row block j of this wave lies j * RPI rows further on, and the
-  // swizzle term (row / RW) % CPR does not depend on j (RPI is a multiple of RW * CPR)
-  static_assert(RPI % (RW * CPR) == 0 && RPI % 2 == 0, "swizzle and row parity repeat per row block");
+  // weight rows need no clamp; the swizzle term (row / RW) % CPR does not depend on the row block j
+  // (RPI is a multiple of RW * CPR)
+  static_assert(RPI % (RW * CPR) == 0, "the swizzle repeats per row block");
   unsigned w_goff[IPW];
-  {
-    const int row = wave * IPW * RPI + r_in;
-    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
-    const unsigned w0 = 2u * (unsigned)((row >> 1) * p.w_lay.pair + (row & 1) * p.w_lay.par + c_sw * 8);
 #pragma unroll
-    for (int j = 0; j < IPW; ++j) w_goff[j] = w0 + (unsigned)(j * RPI * p.w_lay.pair) + (unsigned)(kImmBias - j * 1024);
+  for (int j = 0; j < IPW; ++j) {
+    const int row = (wave * IPW + j) * RPI + r_in;
+    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
+    w_goff[j] = 2u * (unsigned)(operand_row_offset(p.w_lay, row) + c_sw * 8) + (unsigned)(kImmBias - j * 1024);
   }
   const int64_t a_step = 2 * p.a_lay.kb, w_step = 2 * p.w_lay.kb;  // bytes per k-stage
   // the stage being requested: global bases, index and ring slot; past the last stage the bases
   // stay put, so the tail re-fetches the last stage (valid memory, never read)
-  gptr a_req = (gptr)(p.A + (int64_t)(m0 >> 1) * p.a_lay.pair + (int64_t)kt_begin * p.a_lay.kb) - kImmBias;
-  gptr w_req = (gptr)(p.W + (int64_t)(n0 >> 1) * p.w_lay.pair + (int64_t)kt_begin * p.w_lay.kb) - kImmBias;
+  gptr a_req = (gptr)(p.A + operand_row_offset(p.a_lay, m0) + (int64_t)kt_begin * p.a_lay.kb) - kImmBias;
+  gptr w_req = (gptr)(p.W + operand_row_offset(p.w_lay, n0) + (int64_t)kt_begin * p.w_lay.kb) - kImmBias;
   int req_t = 0, req_slot = 0;
   constexpr int N_DMA = IPA + IPW;
   // One DMA instruction: 64 lanes x 16 bytes from (scalar base + per-lane byte offset) into 1 KiB
@@ -600,19 +599,20 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p) {
   for (int j = 0; j < A_LOADS; ++j) {
     int m = m0 + ld_row + 32 * j;
     if (m > p.M - 1) m = p.M - 1;  // rows past M are clamped: computed, never stored
-    a_ptr[j] = p.A + (int64_t)(m >> 1) * p.a_lay.pair + (m & 1) * p.a_lay.par + (ld_chunk >> 2) * p.a_lay.kb +
-               (ld_chunk & 3) * 8;
+    a_ptr[j] = p.A + operand_row_offset(p.a_lay, m) + (ld_chunk >> 2) * p.a_lay.kb + (ld_chunk & 3) * 8;
   }
-  // weight rows 32 j apart keep their parity, so one base pointer and a pair stride serve all of them
-  const bf16* w_ptr = p.W + (int64_t)((n0 + ld_row) >> 1) * p.w_lay.pair + ((n0 + ld_row) & 1) * p.w_lay.par +
-                      (ld_chunk >> 2) * p.w_lay.kb + (ld_chunk & 3) * 8;
+  // weight rows: a wave-uniform base plus a 32-bit offset per row block of 32
+  const bf16* w_ptr = p.W + operand_row_offset(p.w_lay, n0) + (ld_chunk >> 2) * p.w_lay.kb + (ld_chunk & 3) * 8;
+  int w_off[W_LOADS];
+#pragma unroll
+  for (int j = 0; j < W_LOADS; ++j) w_off[j] = (int)operand_row_offset(p.w_lay, ld_row + 32 * j);
 
   bf16x8 a_reg[A_LOADS], w_reg[W_LOADS];
   auto load_global = [&](int kt) {
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) a_reg[j] = ld_bf16x8(a_ptr[j] + (int64_t)kt * 2 * p.a_lay.kb);
 #pragma unroll
-    for (int j = 0; j < W_LOADS; ++j) w_reg[j] = ld_bf16x8(w_ptr + (int64_t)(16 * j) * p.w_lay.pair + (int64_t)kt * 2 * p.w_lay.kb);
+    for (int j = 0; j < W_LOADS; ++j) w_reg[j] = ld_bf16x8(w_ptr + w_off[j] + (int64_t)kt * 2 * p.w_lay.kb);
   };
   auto store_lds = [&](int buf) {
     bf16* a = sA + buf * BM * BK;
@@ -831,7 +831,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.res_f32 = a.residual_f32;
   p.ws = a.workspace;
   p.a_lay = a.a_layout;
-  p.w_lay = layout_paired(a.Kpad);
+  p.w_lay = layout_weights(a.Kpad);
   p.u_lay = a.u_layout;
   p.Kpad = a.Kpad;
   p.Npad = a.Npad;

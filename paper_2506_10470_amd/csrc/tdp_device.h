@@ -39,10 +39,17 @@ __device__ __forceinline__ bf16x8 zero_bf16x8() {
   return z;
 }
 
-// Offset of element (r, k) in an operand laid out as (r>>1)*pair + (k>>5)*kb + (r&1)*par + (k&31).
+// Offset of element (r, k) in an operand laid out as
+// (r >> shift)*group + (k>>5)*kb + (r & (2^shift - 1))*par + (k&31).
 template <typename L>
 __device__ __forceinline__ int64_t operand_offset(const L& lay, int r, int k) {
-  return (int64_t)(r >> 1) * lay.pair + (int64_t)(k >> 5) * lay.kb + (int64_t)(r & 1) * lay.par + (k & 31);
+  return (int64_t)(r >> lay.shift) * lay.group + (int64_t)(k >> 5) * lay.kb +
+         (int64_t)(r & ((1 << lay.shift) - 1)) * lay.par + (k & 31);
+}
+// the row part of that offset alone
+template <typename L>
+__device__ __forceinline__ int64_t operand_row_offset(const L& lay, int r) {
+  return (int64_t)(r >> lay.shift) * lay.group + (int64_t)(r & ((1 << lay.shift) - 1)) * lay.par;
 }
 
 // ---- 8-bit KV cache: OCP E4M3 (sign, 4 exponent bits with bias 7, 3 mantissa bits; exponent field
