@@ -15,16 +15,17 @@ namespace tdp {
 // the layout of the activations the stage's own kernels hand to the GEMMs, which lets a k-stage of 32
 // be fetched with full-line requests.
 // Blocked (groups of R = 2^shift rows, R * 64 contiguous bytes per k step): group = R K, kb = 32 R,
-// par = 32; the layout of the repacked weights, R = 64: a direct-to-LDS instruction (16 rows x 64
+// par = 32; the layout of the repacked weights, R = 128: a direct-to-LDS instruction (16 rows x 64
 // bytes) then covers one contiguous KiB, and a workgroup that streams its rows over k reads HBM in
-// 4 KiB pieces (measured on a 57344 x 8192 matrix: 6.0-6.2 TB/s against 5.3-5.5 with groups of 2).
+// 8 KiB pieces (measured on a 57344 x 8192 matrix: 6.0-6.2 TB/s with groups of 64 or 128 against
+// 5.3-5.5 with groups of 2; in the stage, groups of 128 are 1-2 % ahead of 64 and of 256).
 struct OperandLayout {
   int64_t group, kb, par;
   int shift;
 };
 static inline OperandLayout layout_row_major(int64_t ld) { return OperandLayout{2 * ld, 32, ld, 1}; }
 static inline OperandLayout layout_paired(int64_t K) { return OperandLayout{2 * K, 64, 32, 1}; }
-constexpr int kWeightGroupShift = 6;  // weights: groups of 64 rows
+constexpr int kWeightGroupShift = 7;  // weights: groups of 128 rows
 static inline OperandLayout layout_weights(int64_t K) {
   return OperandLayout{(int64_t)(1 << kWeightGroupShift) * K, 32ll << kWeightGroupShift, 32, kWeightGroupShift};
 }
