@@ -79,6 +79,74 @@ hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float*
   return hipGetLastError();
 }
 
+// The row is formed first: h = residual + the split-K partials of the projection in front of the
+// norm (summed in split order), stored as the fp32 residual stream, then normalised.  A thread
+// re-reads only what it wrote itself.  1024 threads per row: at d = 8192 every thread has one
+// 8-element chunk and all of its loads are in flight at once.
+template <bool F32_RES>
+__global__ __launch_bounds__(1024) void rmsnorm_sum_kernel(const void* __restrict__ residual, int64_t ldr,
+                                                          const float* __restrict__ ws, int splits, int M,
+                                                          int64_t ld_ws, float* __restrict__ h_out, int64_t ldh,
+                                                          const float* __restrict__ gain, float eps, int d,
+                                                          bf16* __restrict__ y, OperandLayout y_lay) {
+  const int row = blockIdx.x;
+  const void* rr = F32_RES ? (const void*)((const float*)residual + (int64_t)row * ldr)
+                           : (const void*)((const bf16*)residual + (int64_t)row * ldr);
+  float* hr = h_out + (int64_t)row * ldh;
+  const int chunks = d / 8;
+  float ss = 0.f;
+  for (int c = threadIdx.x; c < chunks; c += 1024) {
+    float f[8], acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < splits; ++z) {
+      load8<true>(ws + ((int64_t)z * M + row) * ld_ws, c, f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += f[i];
+    }
+    load8<F32_RES>(rr, c, f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      acc[i] += f[i];
+      ss += acc[i] * acc[i];
+    }
+    *reinterpret_cast<f32x4*>(hr + c * 8) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+    *reinterpret_cast<f32x4*>(hr + c * 8 + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+  }
+  __shared__ float red[16];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) tot += red[w];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int c = threadIdx.x; c < chunks; c += 1024) {
+    float f[8];
+    load8<true>(hr, c, f);
+    const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c * 8);
+    const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + c * 8 + 4);
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[i] = (bf16)(f[i] * inv * g0[i]);
+      o[i + 4] = (bf16)(f[i + 4] * inv * g1[i]);
+    }
+    st_bf16x8(y + operand_offset(y_lay, row, c * 8), o);
+  }
+}
+
+hipError_t launch_rmsnorm_sum(const void* residual, int residual_is_f32, int64_t ldr, const float* ws, int splits,
+                              int64_t ld_ws, float* h_out, int64_t ldh, const float* gain, float eps, int M, int d,
+                              void* y, OperandLayout y_layout, hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (residual_is_f32)
+    rmsnorm_sum_kernel<true><<<M, 1024, 0, s>>>(residual, ldr, ws, splits, M, ld_ws, h_out, ldh, gain, eps, d, (bf16*)y,
+                                               y_layout);
+  else
+    rmsnorm_sum_kernel<false><<<M, 1024, 0, s>>>(residual, ldr, ws, splits, M, ld_ws, h_out, ldh, gain, eps, d,
+                                                (bf16*)y, y_layout);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ token -> (sequence, position)
 __device__ __forceinline__ void locate_token(int t, const int32_t* ctx_lens, const int32_t* cu_seqlens,
                                              int n_seqs, int& seq, int& pos) {
@@ -101,13 +169,38 @@ __device__ __forceinline__ void locate_token(int t, const int32_t* ctx_lens, con
 // token's slot of the K pool; v heads are written (transposed) to the V pool.  Rotation pairs
 // channel i with channel i + head_dim/2 and turns the pair by pos * base^(-2i/head_dim); the
 // table holds (cos, sin) of that angle, computed in double precision on the host.
-__global__ __launch_bounds__(256) void rope_kv_kernel(bf16* __restrict__ qkv, int64_t ld, int n_q_heads,
+// PARTIALS: the projection arrives as fp32 split-K partials (summed here in split order, plus the
+// bias) instead of a finished bf16 row; the rotation then works on the unrounded sums.
+template <bool PARTIALS>
+__global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __restrict__ qkv, int64_t ld, int n_q_heads,
                                                       KvLayout kv, const float2* __restrict__ table,
                                                       const int32_t* __restrict__ ctx_lens,
                                                       const int32_t* __restrict__ cu_seqlens, int n_seqs,
                                                       const int32_t* __restrict__ block_tables,
-                                                      int max_pages_per_seq) {
+                                                      int max_pages_per_seq, const float* __restrict__ ws,
+                                                      int splits, int n_tokens, const float* __restrict__ bias) {
   const int t = blockIdx.x;
+  // eight consecutive projection outputs of this token, starting at column col
+  auto proj8 = [&](const bf16* row, int col, float (&f)[8]) {
+    if (PARTIALS) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] = 0.f;
+      for (int z = 0; z < splits; ++z) {
+        float g[8];
+        load8<true>(ws + ((int64_t)z * n_tokens + t) * ld + col, 0, g);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] += g[i];
+      }
+      if (bias) {
+        float g[8];
+        load8<true>(bias + col, 0, g);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] += g[i];
+      }
+    } else {
+      load8<false>(row + col, 0, f);
+    }
+  };
   int seq, pos;
   locate_token(t, ctx_lens, cu_seqlens, n_seqs, seq, pos);
   const int dh = kv.head_dim, half = dh >> 1;
@@ -119,19 +212,19 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(bf16* __restrict__ qkv, in
   const int rot_heads = n_q_heads + kv.n_kv_heads;
   bf16* kpool = (bf16*)kv.k_pool;
   bf16* vpool = (bf16*)kv.v_pool;
-  for (int w = threadIdx.x; w < rot_heads * per_head; w += 256) {
+  for (int w = threadIdx.x; w < rot_heads * per_head; w += blockDim.x) {
     const int head = w / per_head;
     const int c0 = (w % per_head) * 8;
     bf16* hp = row + (int64_t)head * dh;
-    const bf16x8 a = ld_bf16x8(hp + c0);
-    const bf16x8 b = ld_bf16x8(hp + half + c0);
+    float a[8], b[8];
+    proj8(row, head * dh + c0, a);
+    proj8(row, head * dh + half + c0, b);
     float fra[8], frb[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float2 t2 = cs[c0 + i];
-      const float fa = (float)a[i], fb = (float)b[i];
-      fra[i] = fa * t2.x - fb * t2.y;
-      frb[i] = fa * t2.y + fb * t2.x;
+      fra[i] = a[i] * t2.x - b[i] * t2.y;
+      frb[i] = a[i] * t2.y + b[i] * t2.x;
     }
     const int64_t kslot = (((int64_t)page * kv.n_kv_heads + (head - n_q_heads)) * kv.page_size + slot) * dh;
     if (head >= n_q_heads && kv.fp8) {
@@ -164,25 +257,38 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(bf16* __restrict__ qkv, in
       st_bf16x8(dst + half + c0, rb);
     }
   }
-  const bf16* vrow = row + (int64_t)(n_q_heads + kv.n_kv_heads) * dh;
-  for (int w = threadIdx.x; w < kv.n_kv_heads * dh; w += 256) {
-    const int kvh = w / dh, c = w % dh;
-    const int64_t vi = (((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot;
-    if (kv.fp8)
-      ((uint8_t*)kv.v_pool)[vi] = (uint8_t)f32_to_e4m3((float)vrow[w] / kv.v_scale);
-    else
-      vpool[vi] = vrow[w];
+  const int v_col = (n_q_heads + kv.n_kv_heads) * dh;
+  for (int w8 = threadIdx.x; w8 < kv.n_kv_heads * dh / 8; w8 += blockDim.x) {
+    float f[8];
+    proj8(row, v_col + w8 * 8, f);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int w = w8 * 8 + i;
+      const int kvh = w / dh, c = w % dh;
+      const int64_t vi = (((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot;
+      // the value is a bf16 quantity in both forms of the cache (the 8-bit code is taken from it)
+      const bf16 vb = (bf16)f[i];
+      if (kv.fp8)
+        ((uint8_t*)kv.v_pool)[vi] = (uint8_t)f32_to_e4m3((float)vb / kv.v_scale);
+      else
+        vpool[vi] = vb;
+    }
   }
 }
 
 hipError_t launch_rope_kv(void* qkv, int64_t ld, int n_tokens, int n_q_heads, const KvLayout& kv,
                           const float2* rope_table, int max_pos, const int32_t* ctx_lens,
                           const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
-                          int max_pages_per_seq, hipStream_t s) {
+                          int max_pages_per_seq, const float* ws, int splits, const float* bias, hipStream_t s) {
   (void)max_pos;
   if (n_tokens <= 0) return hipSuccess;
-  rope_kv_kernel<<<n_tokens, 256, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
-                                          n_seqs, block_tables, max_pages_per_seq);
+  if (splits > 1)
+    rope_kv_kernel<true><<<n_tokens, 1024, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
+                                                  n_seqs, block_tables, max_pages_per_seq, ws, splits, n_tokens, bias);
+  else
+    rope_kv_kernel<false><<<n_tokens, 256, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
+                                                   n_seqs, block_tables, max_pages_per_seq, nullptr, 1, n_tokens,
+                                                   nullptr);
   return hipGetLastError();
 }
 

@@ -59,6 +59,11 @@ struct GemmArgs {
   int64_t workspace_elems;
   int force_tile;         // 0 = choose; else 1..4 selects a tile shape (tests / tuning)
   int force_splits;       // 0 = choose
+  // Deferred reduction (plain and residual epilogues only): when the plan splits K, leave the fp32
+  // partials in the workspace, ws[(z * M + m) * Npad + n] for split z, apply nothing and launch no
+  // reduce kernel; *splits_used (host) receives the number of splits, 1 meaning `out` was written as
+  // usual.  The consumer (launch_rmsnorm_sum, launch_rope_kv with partials) sums them.
+  int* splits_used;       // null = reduce here
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 hipError_t gemm_setup();  // one-time function attributes (dynamic LDS size)
@@ -82,6 +87,12 @@ hipError_t launch_argmax_rows(const float* logits, int64_t ld, int M, int n, int
 hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float* gain, float eps, int M, int d,
                           void* y, OperandLayout y_layout, hipStream_t s);
 
+// The same with the row formed on the fly from split-K partials: h[m] = residual[m] + sum_z ws[(z*M+m)*ld_ws + :],
+// written to h_out (fp32, leading dimension ldh) and normalised into y.
+hipError_t launch_rmsnorm_sum(const void* residual, int residual_is_f32, int64_t ldr, const float* ws, int splits,
+                              int64_t ld_ws, float* h_out, int64_t ldh, const float* gain, float eps, int M, int d,
+                              void* y, OperandLayout y_layout, hipStream_t s);
+
 // ---- RoPE + KV append ------------------------------------------------------------------------
 struct KvLayout {
   void* k_pool;   // [num_pages][Hkv][page][dh]
@@ -92,10 +103,12 @@ struct KvLayout {
 };
 // decode: token b sits at position ctx_lens[b] of sequence b.  prefill: token t of sequence s
 // (cu_seqlens[s] <= t < cu_seqlens[s+1]) sits at position t - cu_seqlens[s].
+// With splits > 1 the projection is read as fp32 split-K partials, ws[(z * n_tokens + t) * ld + :] (+ bias if
+// given), instead of the bf16 row qkv[t]; the rotated queries are written to qkv either way.
 hipError_t launch_rope_kv(void* qkv, int64_t ld, int n_tokens, int n_q_heads, const KvLayout& kv,
                           const float2* rope_table, int max_pos, const int32_t* ctx_lens,
                           const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
-                          int max_pages_per_seq, hipStream_t s);
+                          int max_pages_per_seq, const float* ws, int splits, const float* bias, hipStream_t s);
 // KV import/export between packed logical order [tokens][Hkv][dh] and the paged pools.
 hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const KvLayout& kv,
                           const int32_t* cu_seqlens, int n_seqs, int total_tokens,
