@@ -340,6 +340,16 @@ def test_decode_70b_shaped_layer_gqa(tdp):
     run_decode_case(tdp, "70b_quarter", ctx, n_layers=1)
 
 
+@pytest.mark.parametrize("shape", ["7b_quarter", "qwen32b_quarter"])
+def test_decode_batch_200_two_layers_split_k_summed_by_the_consumers(tdp, shape):
+    """At 192 rows and more the projections whose K range is split leave their partial sums to the
+    next kernel (RoPE + KV append sums the QKV partials and adds the bias, the following RMSNorm sums
+    the O and down partials together with the residual); two layers so that the second layer's first
+    norm is fed that way.  Contexts up to 300 tokens."""
+    ctx = np.minimum(W.decode_ctx_lens(shape, 200), 300)
+    run_decode_case(tdp, shape, ctx, n_layers=2)
+
+
 def test_a_dropped_bias_would_be_caught(tdp):
     """The biased stage must differ from the same stage without biases by far more than the
     tolerance: otherwise the bias tests above would pass vacuously."""
