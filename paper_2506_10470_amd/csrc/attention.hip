@@ -32,21 +32,23 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf: exp2 gives exa
 // items[i] = (request, span index, tokens to attend to = ctx + 1, 0) for i < n_items[0], and
 // (-1, ...) for the rest of the list up to max_items, so a workgroup learns everything about its
 // work - or that it has none - from one 16-byte record.  One workgroup, any batch size.
-// Longest work first: all full spans, then the requests' last (partial) spans by quarter of
-// span_len, longest quarter first, so the workgroups that run at the end of the launch are short.
+// Longest work first: all full spans, then the requests' last (partial) spans by sixteenth of
+// span_len, longest sixteenth first, so the workgroups that run at the end of the launch are short
+// (with quarters the launch ended on workgroups of up to a quarter span in random order).
 __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restrict__ ctx_lens, int batch, int span_len,
                                                         int4* __restrict__ items, int max_items,
                                                         int32_t* __restrict__ n_items) {
-  constexpr int NB = 5;  // class 0: full spans; 1..4: last span with > 3/4, > 1/2, > 1/4, > 0 of span_len
+  constexpr int NP = 16;      // parts of a span
+  constexpr int NB = NP + 1;  // class 0: full spans; 1..NP: last span with > (NP-c)/NP of span_len
   __shared__ int part[NB][256];
   __shared__ int s_total;
   const int tid = threadIdx.x;
   const int per = (batch + 255) / 256;
   const int b0 = tid * per, b1 = min(b0 + per, batch);
-  const int quarter = span_len / 4;
+  const int piece = span_len / NP;
   auto last_class = [&](int n_total, int n) {  // tokens in the last span: 1 .. span_len
     const int rem = n_total - (n - 1) * span_len;
-    return 4 - min((rem - 1) / quarter, 3);
+    return NP - min((rem - 1) / piece, NP - 1);
   };
   for (int c = 0; c < NB; ++c) part[c][tid] = 0;
   for (int b = b0; b < b1; ++b) {
@@ -56,18 +58,30 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t* __restric
     part[last_class(n_total, n)][tid] += 1;
   }
   __syncthreads();
+  // exclusive prefix over (class, thread): thread c scans class c, then the class totals are chained
+  __shared__ int class_total[NB];
+  if (tid < NB) {
+    int acc = 0;
+    for (int i = 0; i < 256; ++i) {
+      const int v = part[tid][i];
+      part[tid][i] = acc;
+      acc += v;
+    }
+    class_total[tid] = acc;
+  }
+  __syncthreads();
   if (tid == 0) {
     int acc = 0;
-    for (int c = 0; c < NB; ++c)
-      for (int i = 0; i < 256; ++i) {
-        const int v = part[c][i];
-        part[c][i] = acc;
-        acc += v;
-      }
+    for (int c = 0; c < NB; ++c) {
+      const int v = class_total[c];
+      class_total[c] = acc;
+      acc += v;
+    }
     n_items[0] = acc;
     s_total = acc;
   }
   __syncthreads();
+  for (int c = 0; c < NB; ++c) part[c][tid] += class_total[c];
   for (int b = b0; b < b1; ++b) {
     const int n_total = ctx_lens[b] + 1;
     const int n = (n_total + span_len - 1) / span_len;
