@@ -397,8 +397,10 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   for (int j = 0; j < IPA; ++j) {
     const int row = (wave * IPA + j) * RPI + r_in;
     const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
+    // rows past M are computed but never stored; they re-read the tile's valid rows in turn (all of
+    // them reading the last valid row makes one hot line for every workgroup of the launch)
     int m = row;
-    if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
+    if (m0 + m > p.M - 1) m = row % (p.M - m0);
     a_goff[j] = 2u * (unsigned)(operand_row_offset(p.a_lay, m) + c_sw * 8) + (unsigned)(kImmBias - j * 1024);
   }
   // weight rows need no clamp; the swizzle term (row / RW) % CPR does not depend on the row block j
@@ -824,7 +826,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     // 128-row tiles (twice the workgroups, half the split-K factor); measured at M = 256, K = 8192:
     // 59 vs 72 us (N 10240), 50 vs 61 (N 8192); with K = 28672 the 256-row tile stays ahead (141 vs 148)
     const bool narrow = a.Npad <= 16384 && a.Kpad <= 16384;
-    t = a.M <= 32 ? 4 : a.M <= 128 ? 14 : (a.M <= 256 && narrow) ? 14 : 13;
+    // (down to a single row the direct-to-LDS kernel streams the weights as fast as or faster than the
+    // register-staged 32-row one, tile 4: 5.8 vs 5.7 TB/s on gate/up, 4.1-4.6 vs 4.0-4.5 on the small projections)
+    t = a.M <= 128 ? 14 : (a.M <= 256 && narrow) ? 14 : 13;
   }
   const TileInfo& ti = kTiles[t];
   GemmParams p;
@@ -882,7 +886,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
       for (int x = 0; x < 8; ++x) mx = load[x] > mx ? load[x] : mx;
       const int slots = 32 * ti.wg_per_cu;
       const double rounds = (double)((mx + slots - 1) / slots);
-      double cost = rounds * per;
+      // a workgroup pays its pipeline fill and its epilogue whatever its share of K: about 6 k-tiles' worth
+      // (without this term the model splits a 224-tile launch eight ways to fill 256 CUs: measured 25 % slower)
+      double cost = rounds * (per + 6.0);
       // fp32 partials: 8 bytes per element and split at ~4 TB/s, in units of one k-tile round (~1.8 us)
       if (real_sp > 1) cost += 1.1e-6 * real_sp * a.M * (double)a.Npad + 2.0;
       cost *= 1.0 + 0.02 * (5 - __builtin_ctz(sb_size));  // prefer larger super-blocks on ties
