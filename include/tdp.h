@@ -188,7 +188,7 @@ TDP_API int tdp_stage_set_layer_range(tdp_stage* st, int32_t first, int32_t coun
  * Diagnostic: one projection GEMM through the library's kernels, out = A * W with W given as
  * a row-major [K, N] bf16 device matrix (repacked internally on every call: not a fast path).
  * A dev bf16 [M][K]; out dev bf16 [M][N].  K multiple of 64, N multiple of 4.
- * tile: 0 = automatic, 1..15 force a kernel variant; splits: 0 = automatic, else force the split-K
+ * tile: 0 = automatic, 1..16 force a kernel variant; splits: 0 = automatic, else force the split-K
  * factor.  epilogue: 0 = plain store, 1 = out = residual + A*W (residual dev bf16 [M][N]).
  */
 TDP_API int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out, int32_t M, int32_t N,

@@ -16,6 +16,10 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <initializer_list>
+#include <mutex>
+#include <unordered_map>
+
 #include "tdp_device.h"
 #include "tdp_kernels.h"
 
@@ -351,10 +355,10 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_dma_ker
 // MFMA-only loop sustains 2.16 PFLOP/s with 16x16x32 against 1.89 with 32x32x16 (measured).
 // Fragments of stage t+1 are read under the MFMAs of stage t (two register sets, the stage loop
 // is unrolled by two); one barrier per stage, at its start.
-template <int BM, int NS, int TM, int TN>
-__global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_kernel(const GemmParams p) {
-  constexpr int BN = 256, BK = 32;
-  constexpr int WAVES_N = 8 / TN, WAVES = (BM / (TM * 32)) * WAVES_N;
+template <int BM, int NS, int TM, int TN, int BN = 256>
+__global__ __launch_bounds__((BM / (TM * 32)) * (BN / 32 / TN) * 64) void gemm_mi16_kernel(const GemmParams p) {
+  constexpr int BK = 32;
+  constexpr int WAVES_N = BN / 32 / TN, WAVES = (BM / (TM * 32)) * WAVES_N;
   constexpr int CPR = BK / 8;         // 16-byte chunks per row
   constexpr int RW = 256 / (BK * 2);  // rows per 256-byte bank window
   constexpr int RPI = 64 / CPR;       // rows per DMA instruction
@@ -472,7 +476,7 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_mi16_ke
   const int a_off = (wm0 + l16) * BK + swz;
   bf16x8 wf[2][WT], af[2][AT];
   constexpr int PENDING = (NS - 2) * N_DMA;
-  static_assert(WT == 8 && N_DMA <= WT && AT <= WT, "one weight tile, one DMA and at most one activation tile per MFMA group");
+  static_assert(N_DMA <= WT && AT <= WT && AT >= 4, "one weight tile, one DMA and at most one activation tile per MFMA group");
   int rd_slot = 0;  // ring slot of the stage whose fragments are read next
   int w_next = w_off, a_next = a_off;  // this lane's fragments in that slot (element offsets into smem)
   auto read_frags = [&](int set) {
@@ -750,7 +754,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
 struct TileInfo {
   int bm, bn, lds_bytes, wg_per_cu;
 };
-static const TileInfo kTiles[16] = {
+static const TileInfo kTiles[17] = {
     {0, 0, 0, 0},
     {256, 256, 2 * (256 + 256) * 128, 1},
     {128, 128, 2 * (128 + 128) * 128, 2},
@@ -767,6 +771,7 @@ static const TileInfo kTiles[16] = {
     {256, 256, 4 * 512 * 64, 1},   // 13: as 9 on 16x16x32 MFMA tiles
     {128, 256, 6 * 384 * 64, 1},   // 14: as 11 on 16x16x32 MFMA tiles
     {256, 256, 5 * 512 * 64, 1},   // 15: as 10 on 16x16x32 MFMA tiles
+    {128, 128, 4 * 256 * 64, 2},   // 16: 128 x 128 tile on 16x16x32 MFMA tiles, BK 32 x 4 stages, two workgroups per CU
 };
 
 hipError_t gemm_setup() {
@@ -815,13 +820,16 @@ hipError_t gemm_setup() {
   if (e != hipSuccess) return e;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<256, 5, 4, 4>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[15].lds_bytes);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<128, 4, 2, 2, 128>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[16].lds_bytes);
   return e;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   int t = a.force_tile;
-  if (t < 1 || t > 15) {
+  if (t < 1 || t > 16) {
     // up to 256 rows a projection with few weight rows and a short K fills the chip better with
     // 128-row tiles (twice the workgroups, half the split-K factor); measured at M = 256, K = 8192:
     // 59 vs 72 us (N 10240), 50 vs 61 (N 8192); with K = 28672 the 256-row tile stays ahead (141 vs 148)
@@ -857,47 +865,85 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   // The model: an XCD (32 CUs) works through the tiles dealt to it, wg_per_cu * 32 at a time, and a
   // tile costs its k-tiles; split-K adds the fp32 partial round trip.  Small problems (decode) want
   // every XCD equally loaded; large ones want 32-tile super-blocks for L2 reuse.
-  int max_splits = 1;
-  if (a.force_splits > 0) max_splits = a.force_splits;
-  else if (a.M <= 512) max_splits = p.k_tiles_total / 4 < 16 ? (p.k_tiles_total / 4 > 0 ? p.k_tiles_total / 4 : 1) : 16;
-  if (max_splits > p.k_tiles_total) max_splits = p.k_tiles_total;
-  double best_cost = 1e300;
-  int best_splits = 1, best_sb = 1;
-  for (int sp = a.force_splits > 0 ? max_splits : 1; sp <= max_splits; ++sp) {
-    if (sp > 1 && (int64_t)sp * a.M * a.Npad > a.workspace_elems) break;
-    const int per = (p.k_tiles_total + sp - 1) / sp;
-    const int real_sp = (p.k_tiles_total + per - 1) / per;
-    if (real_sp != sp && a.force_splits <= 0) continue;  // same schedule as a smaller factor
-    for (int sb_size = 32; sb_size >= 1; sb_size >>= 1) {
-      int sb_m = p.tiles_m >= 4 ? 4 : p.tiles_m >= 2 ? 2 : 1;
-      if (sb_m > sb_size) sb_m = sb_size;
-      const int sb_n = sb_size / sb_m;
-      const int n_sb_n = (p.tiles_n + sb_n - 1) / sb_n;
-      const int n_sb_m = (p.tiles_m + sb_m - 1) / sb_m;
-      const int n_sb = n_sb_m * n_sb_n;
-      int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      for (int g = 0; g < n_sb * real_sp; ++g) {
-        const int sb = g % n_sb;
-        const int rows = (sb / n_sb_n + 1) * sb_m <= p.tiles_m ? sb_m : p.tiles_m - (sb / n_sb_n) * sb_m;
-        const int cols = (sb % n_sb_n + 1) * sb_n <= p.tiles_n ? sb_n : p.tiles_n - (sb % n_sb_n) * sb_n;
-        load[g & 7] += (int64_t)rows * cols;
-      }
-      int64_t mx = 0;
-      for (int x = 0; x < 8; ++x) mx = load[x] > mx ? load[x] : mx;
-      const int slots = 32 * ti.wg_per_cu;
-      const double rounds = (double)((mx + slots - 1) / slots);
-      // a workgroup pays its pipeline fill and its epilogue whatever its share of K: about 6 k-tiles' worth
-      // (without this term the model splits a 224-tile launch eight ways to fill 256 CUs: measured 25 % slower)
-      double cost = rounds * (per + 6.0);
-      // fp32 partials: 8 bytes per element and split at ~4 TB/s, in units of one k-tile round (~1.8 us)
-      if (real_sp > 1) cost += 1.1e-6 * real_sp * a.M * (double)a.Npad + 2.0;
-      cost *= 1.0 + 0.02 * (5 - __builtin_ctz(sb_size));  // prefer larger super-blocks on ties
-      if (cost < best_cost) {
-        best_cost = cost;
-        best_splits = real_sp;
-        best_sb = sb_size;
+  // The search below costs tens of microseconds on the host and its answer depends only on the
+  // problem's shape, so it is remembered (a serving loop asks for the same few shapes every step).
+  struct PlanKey {
+    int M, t, force_splits;
+    int64_t Npad, Kpad, ws_elems;
+    bool operator==(const PlanKey& o) const {
+      return M == o.M && t == o.t && force_splits == o.force_splits && Npad == o.Npad && Kpad == o.Kpad &&
+             ws_elems == o.ws_elems;
+    }
+  };
+  struct PlanKeyHash {
+    size_t operator()(const PlanKey& k) const {
+      uint64_t h = 0x9e3779b97f4a7c15ull;
+      for (uint64_t v : {(uint64_t)k.M, (uint64_t)k.t, (uint64_t)k.force_splits, (uint64_t)k.Npad, (uint64_t)k.Kpad,
+                         (uint64_t)k.ws_elems})
+        h = (h ^ v) * 0xff51afd7ed558ccdull + (h >> 29);
+      return (size_t)h;
+    }
+  };
+  struct PlanEntry {
+    int splits, sb;
+  };
+  static std::mutex plan_mutex;
+  static std::unordered_map<PlanKey, PlanEntry, PlanKeyHash> plan_cache;
+  const PlanKey key{a.M, t, a.force_splits, a.Npad, a.Kpad, a.workspace_elems};
+  int best_splits = 0, best_sb = 1;
+  {
+    std::lock_guard<std::mutex> lock(plan_mutex);
+    const auto it = plan_cache.find(key);
+    if (it != plan_cache.end()) {
+      best_splits = it->second.splits;
+      best_sb = it->second.sb;
+    }
+  }
+  if (best_splits == 0) {
+    best_splits = 1;
+    int max_splits = 1;
+    if (a.force_splits > 0) max_splits = a.force_splits;
+    else if (a.M <= 512) max_splits = p.k_tiles_total / 4 < 16 ? (p.k_tiles_total / 4 > 0 ? p.k_tiles_total / 4 : 1) : 16;
+    if (max_splits > p.k_tiles_total) max_splits = p.k_tiles_total;
+    double best_cost = 1e300;
+    for (int sp = a.force_splits > 0 ? max_splits : 1; sp <= max_splits; ++sp) {
+      if (sp > 1 && (int64_t)sp * a.M * a.Npad > a.workspace_elems) break;
+      const int per = (p.k_tiles_total + sp - 1) / sp;
+      const int real_sp = (p.k_tiles_total + per - 1) / per;
+      if (real_sp != sp && a.force_splits <= 0) continue;  // same schedule as a smaller factor
+      for (int sb_size = 32; sb_size >= 1; sb_size >>= 1) {
+        int sb_m = p.tiles_m >= 4 ? 4 : p.tiles_m >= 2 ? 2 : 1;
+        if (sb_m > sb_size) sb_m = sb_size;
+        const int sb_n = sb_size / sb_m;
+        const int n_sb_n = (p.tiles_n + sb_n - 1) / sb_n;
+        const int n_sb_m = (p.tiles_m + sb_m - 1) / sb_m;
+        const int n_sb = n_sb_m * n_sb_n;
+        int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int g = 0; g < n_sb * real_sp; ++g) {
+          const int sb = g % n_sb;
+          const int rows = (sb / n_sb_n + 1) * sb_m <= p.tiles_m ? sb_m : p.tiles_m - (sb / n_sb_n) * sb_m;
+          const int cols = (sb % n_sb_n + 1) * sb_n <= p.tiles_n ? sb_n : p.tiles_n - (sb % n_sb_n) * sb_n;
+          load[g & 7] += (int64_t)rows * cols;
+        }
+        int64_t mx = 0;
+        for (int x = 0; x < 8; ++x) mx = load[x] > mx ? load[x] : mx;
+        const int slots = 32 * ti.wg_per_cu;
+        const double rounds = (double)((mx + slots - 1) / slots);
+        // a workgroup pays its pipeline fill and its epilogue whatever its share of K: about 6 k-tiles' worth
+        // (without this term the model splits a 224-tile launch eight ways to fill 256 CUs: measured 25 % slower)
+        double cost = rounds * (per + 6.0);
+        // fp32 partials: 8 bytes per element and split at ~4 TB/s, in units of one k-tile round (~1.8 us)
+        if (real_sp > 1) cost += 1.1e-6 * real_sp * a.M * (double)a.Npad + 2.0;
+        cost *= 1.0 + 0.02 * (5 - __builtin_ctz(sb_size));  // prefer larger super-blocks on ties
+        if (cost < best_cost) {
+          best_cost = cost;
+          best_splits = real_sp;
+          best_sb = sb_size;
+        }
       }
     }
+    std::lock_guard<std::mutex> lock(plan_mutex);
+    if (plan_cache.size() < 65536) plan_cache[key] = PlanEntry{best_splits, best_sb};
   }
   int splits = best_splits;
   p.k_tiles_per_split = (p.k_tiles_total + splits - 1) / splits;
@@ -928,7 +974,8 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     case 12: gemm_dma_kernel<64, 32, 4, 2, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
     case 13: gemm_mi16_kernel<256, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
     case 14: gemm_mi16_kernel<128, 6, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    default: gemm_mi16_kernel<256, 5, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 15: gemm_mi16_kernel<256, 5, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    default: gemm_mi16_kernel<128, 4, 2, 2, 128><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -501,7 +501,7 @@ int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out,
   if (M < 0 || N <= 0 || K <= 0) return fail(TDP_EINVAL, "bad GEMM shape");
   if (K % 64 || N % 4) return fail(TDP_EINVAL, "K must be a multiple of 64 and N of 4");
   if (epilogue != 0 && epilogue != 1) return fail(TDP_EINVAL, "epilogue must be 0 or 1");
-  if (tile < 0 || tile > 15 || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
+  if (tile < 0 || tile > 16 || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
   if (M == 0) return TDP_OK;
   if (!A || !W || !out || (epilogue == 1 && !residual)) return fail(TDP_EINVAL, "null pointer");
   hipStream_t s = (hipStream_t)stream;

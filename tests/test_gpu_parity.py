@@ -176,9 +176,10 @@ def run_prefill_case(tdp, shape_name, seq_lens, n_layers=None, stream_id=2, deco
     (4, 768, 256, 0, 0, 0), (4, 256, 704, 0, 0, 1), (33, 320, 128, 4, 2, 0), (64, 512, 512, 3, 1, 1),
     (100, 384, 256, 2, 3, 0), (130, 1024, 320, 2, 1, 1), (300, 768, 1024, 1, 1, 0), (257, 516, 192, 1, 2, 1),
     (512, 1280, 2048, 0, 0, 0), (1000, 256, 64, 0, 0, 1),
-    # the direct-to-LDS variants: 32x32x16 tiles (9, 11, 12) and 16x16x32 tiles (13, 14, 15), ragged M, split-K
+    # the direct-to-LDS variants: 32x32x16 tiles (9, 11, 12) and 16x16x32 tiles (13, 14, 15, 16), ragged M, split-K
     (513, 520, 448, 9, 2, 1), (70, 260, 128, 11, 1, 0), (65, 512, 256, 12, 2, 1),
     (300, 768, 1024, 13, 1, 0), (257, 516, 192, 13, 2, 1), (100, 384, 256, 14, 3, 0), (130, 1024, 320, 15, 1, 1),
+    (100, 384, 256, 16, 2, 0), (300, 640, 1024, 16, 1, 1), (7, 256, 512, 16, 4, 1),
 ])
 def test_gemm_matches_fp64_product(tdp, M, N, K, tile, splits, epi):
     g = torch.Generator(device="cpu").manual_seed(M * 131 + N)
