@@ -351,6 +351,13 @@ def test_decode_batch_200_two_layers_split_k_summed_by_the_consumers(tdp, shape)
     run_decode_case(tdp, shape, ctx, n_layers=2)
 
 
+@pytest.mark.parametrize("shape", ["7b_quarter", "qwen32b_quarter"])
+def test_prefill_292_tokens_two_layers_split_k_summed_by_the_consumers(tdp, shape):
+    """A short prefill (192 to 512 packed tokens) also splits K and leaves the sums to RoPE and to
+    the norms; four prompts of ragged length, two layers, one decode step behind it."""
+    run_prefill_case(tdp, shape, [120, 31, 77, 64], n_layers=2, decode_steps=1)
+
+
 def test_a_dropped_bias_would_be_caught(tdp):
     """The biased stage must differ from the same stage without biases by far more than the
     tolerance: otherwise the bias tests above would pass vacuously."""
