@@ -252,6 +252,55 @@ def ends_section(tdp, W, shape, batch, i32, vocab=32000):
             "lm_head_weight_gbs": round(vocab * shape.d_model * 2 / t_head / 1e6, 1)}
 
 
+def engine_section(tdp, W, Stage, shape, decode_sweep, prefill_curve, i32, n_requests=256, n_stages=4, vocab=32000):
+    """The decisions of Sec. 3.3 - 3.5 driving the real stage on this one GPU: tdp_simulate_exec plans a
+    4-stage temporally-disaggregated pipeline on the measured profile and a StageWorker executes every batch
+    of the schedule with the HIP kernels (token embedding -> stage -> vocabulary projection -> greedy token),
+    one after the other.  The wall time is therefore that of ONE GPU doing every batch's work in turn, not a
+    pipeline's; it shows the whole path running from token ids to token ids under the paper's scheduling."""
+    import torch
+    from paper_2506_10470_amd import tdp_sched as L
+    from paper_2506_10470_amd.engine import StageWorker
+
+    dec = [(float(s["batch"]), float(s["ms_per_step"])) for s in decode_sweep]
+    pre = [(float(c["tokens"]), float(c["ms"])) for c in prefill_curve]
+    reqs = [(int(a), int(min(b, 128)), int(min(c, 128))) for a, b, c in W.serving_requests(n_requests)]
+    prompts = [W.token_ids(vocab, r[0], 1000 + i) for i, r in enumerate(reqs)]
+    budget = 4096
+    capacity = 48 * 1024                      # tokens: small enough that the run switches phases several times
+    max_len = max(r[0] + r[1] for r in reqs) + 1
+    max_pps = (max_len + 15) // 16 + 1
+    num_pages = capacity // 16 + n_requests
+    max_tokens = max(budget, max_len)
+    st = Stage(tdp, shape, num_pages, n_requests, max_tokens, n_requests, max_pps, load_weights=True)
+    ends = tdp.tdp_ends_create(tdp.EndsConfig(vocab, shape.d_model, shape.rms_eps, max(max_tokens, n_requests)))
+    for which, name, dt, rows, cols in ((tdp.E_EMBEDDING, "embedding", tdp.BF16, vocab, shape.d_model),
+                                        (tdp.E_LM_HEAD, "lm_head", tdp.BF16, shape.d_model, vocab),
+                                        (tdp.E_FINAL_NORM, "final_norm", tdp.F32, shape.d_model, 1)):
+        w = W.ends_weight(shape, name, vocab, device="cuda", dtype=torch.float32 if dt == tdp.F32 else torch.bfloat16)
+        tdp.tdp_ends_set_weight(ends, which, w, dt, tdp.DEVICE, rows, cols)
+        del w
+    worker = StageWorker(tdp, st.h, ends, shape.d_model, num_pages, max_pps, n_requests, max_tokens, n_requests, prompts)
+    cfg = L.SimConfig(n_stages, capacity, budget, 1, 1, 1, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    res, _ = worker.run(L, cfg, reqs, dec, pre)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ok = [len(g) for g in worker.generated] == [r[1] for r in reqs] and len(worker.free_pages) == num_pages
+    tdp.tdp_ends_destroy(ends)
+    st.close()
+    torch.cuda.empty_cache()
+    return {"n_requests": n_requests, "n_stages_planned": n_stages, "kv_capacity_tokens": capacity, "vocab": vocab,
+            "generated_tokens": int(res.generated_tokens), "prefill_tokens": int(res.prefill_tokens),
+            "phase_switches": int(res.phase_switches), "recomputes": int(res.recomputes),
+            "prefill_batches": worker.stats["prefill_batches"], "decode_steps": worker.stats["decode_steps"],
+            "wall_s_one_gpu_sequential": round(wall, 3),
+            "tok_s_one_gpu_sequential": round(res.generated_tokens / wall, 1),
+            "planned_pipeline_tok_s": round(res.generated_tokens / (res.total_ms * 1e-3), 1),
+            "all_requests_complete_and_pages_returned": bool(ok)}
+
+
 def scheduler_section(shape, decode_sweep, prefill_curve, n_requests=20000, n_stages=4):
     """The paper's three scheduling decisions (Sec. 3.3 - 3.5) driving a simulated pipeline of
     `n_stages` copies of this stage, timed by the profile measured above: 20000 synthetic requests
@@ -459,6 +508,12 @@ def main():
         result["scheduler"] = scheduler_section(shape, result["decode_sweep"], result["prefill"]["curve"])
         log("scheduler (simulated 4-stage pipeline on the measured profile): %s" % json.dumps(
             {k: v["tok_s"] for k, v in result["scheduler"]["policies"].items()}))
+    if "decode_sweep" in result and "prefill" in result and not args.layers:
+        result["engine"] = engine_section(tdp, W, Stage, shape, result["decode_sweep"], result["prefill"]["curve"], i32)
+        log("engine (schedule executed with the real kernels, %d requests): %s" % (
+            result["engine"]["n_requests"], json.dumps({k: result["engine"][k] for k in (
+                "generated_tokens", "decode_steps", "prefill_batches", "phase_switches", "recomputes",
+                "wall_s_one_gpu_sequential", "tok_s_one_gpu_sequential")})))
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(shape, dec_ctx, cu)
         log("cpu oracle: %s tok/s (%s)" % (result["cpu_baseline"]["value"], result["cpu_baseline"]["sample"]))

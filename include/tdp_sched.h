@@ -27,6 +27,7 @@ extern "C" {
 
 #define TDP_SCHED_API __attribute__((visibility("default")))
 #define TDP_SCHED_EINVAL (-1)
+#define TDP_SCHED_EABORT (-2) /* an executor callback returned nonzero: the run stopped there */
 
 TDP_SCHED_API int tdp_sched_abi_version(void); /* 1 */
 
@@ -116,6 +117,33 @@ TDP_SCHED_API int tdp_simulate(const tdp_sim_config* cfg, const int32_t* input_l
                                const double* decode_ms, int32_t n_decode, const double* prefill_x,
                                const double* prefill_ms, int32_t n_prefill, tdp_sim_result* result,
                                tdp_sim_event* events, int64_t events_cap);
+
+/* ---- the same run with the work done for real ----------------------------------------------------
+ * tdp_simulate_exec takes the same decisions in the same order (the pipeline clock still comes from
+ * the two profiles) and, at every event, calls the executor so that a worker can run the batch the
+ * event stands for: this is how the decisions of Sec. 3.3 - 3.5 drive the stage library (tdp.h) on
+ * one GPU.  Callbacks run on the calling thread, between decisions; any of them may be null; a
+ * nonzero return stops the run (TDP_SCHED_EABORT).  exec = null is tdp_simulate.
+ *   prefill(user, ids, input_len, n)   a prefill batch, in packing order; input_len[i] tokens of request
+ *                                      ids[i] are to be prefilled from position 0 (for a request that was
+ *                                      evicted earlier: its prompt plus everything it had generated) and
+ *                                      yield its next token
+ *   decode(user, batch, ids, context, n)  one decode step of pipeline batch `batch`: request ids[i] holds
+ *                                      context[i] tokens in the cache, its newest token goes in at that
+ *                                      position and the step yields the next one
+ *   release(user, ids, n, reason)      the requests leave the cache: reason 0 = finished, 1 = evicted
+ *                                      (memory overflow: they will be prefilled again later) */
+typedef struct {
+  void* user;
+  int (*prefill)(void* user, const int64_t* ids, const int32_t* input_len, int32_t n);
+  int (*decode)(void* user, int32_t batch, const int64_t* ids, const int32_t* context, int32_t n);
+  int (*release)(void* user, const int64_t* ids, int32_t n, int32_t reason);
+} tdp_sim_executor;
+TDP_SCHED_API int tdp_simulate_exec(const tdp_sim_config* cfg, const int32_t* input_len, const int32_t* output_len,
+                                    const int32_t* predict_len, int64_t n_requests, const double* decode_x,
+                                    const double* decode_ms, int32_t n_decode, const double* prefill_x,
+                                    const double* prefill_ms, int32_t n_prefill, tdp_sim_result* result,
+                                    tdp_sim_event* events, int64_t events_cap, const tdp_sim_executor* exec);
 
 #ifdef __cplusplus
 }

@@ -147,6 +147,8 @@ struct Simulation {
   tdp_sim_result res{};
   tdp_sim_event* events = nullptr;
   int64_t events_cap = 0;
+  const tdp_sim_executor* exec = nullptr;  // optional: does the work each event stands for
+  bool aborted = false;
 
   Simulation(const tdp_sim_config& c, Profile d, Profile p) : cfg(c), dec(d), pre(p) {}
 
@@ -206,6 +208,11 @@ struct Simulation {
                   running.end());
   }
 
+  bool abort_run() {
+    aborted = true;
+    return false;
+  }
+
   bool run() {
     const int n = cfg.n_stages;
     stage_free.assign((size_t)n, 0.0);
@@ -218,6 +225,8 @@ struct Simulation {
         const double finish = run_batch(std::max(now, stage_free[0]), pre.time((double)b.tokens));
         event(0, finish, b.count, b.tokens);
         res.prefill_tokens += b.tokens;
+        std::vector<int64_t> ids;
+        std::vector<int32_t> lens;
         for (int64_t k = 0; k < b.count; ++k) {
           const int64_t id = waiting.front();
           waiting.pop_front();
@@ -226,7 +235,11 @@ struct Simulation {
           ++res.generated_tokens;
           kv += r.input_len + 1;
           running.push_back(id);
+          ids.push_back(id);
+          lens.push_back((int32_t)r.input_len);
         }
+        if (exec && exec->prefill && exec->prefill(exec->user, ids.data(), lens.data(), (int32_t)ids.size()) != 0)
+          return abort_run();
         last_finish = std::max(last_finish, finish);
       }
       res.peak_kv_tokens = std::max(res.peak_kv_tokens, kv);
@@ -237,7 +250,12 @@ struct Simulation {
             gone.insert(id);
             kv -= req[(size_t)id].input_len + req[(size_t)id].generated;
           }
-        if (!gone.empty()) remove_running(gone);
+        if (!gone.empty()) {
+          const std::vector<int64_t> ids(gone.begin(), gone.end());
+          if (exec && exec->release && exec->release(exec->user, ids.data(), (int32_t)ids.size(), 0) != 0)
+            return abort_run();
+          remove_running(gone);
+        }
       }
       if (running.empty()) {
         if (plan.empty()) return false;  // a prompt does not fit the capacity on its own
@@ -265,6 +283,11 @@ struct Simulation {
         now = t_ret;
         std::vector<int64_t>& batch = ws.batches[(size_t)i];
         const double step_ms = dec.time((double)batch.size());
+        if (exec && exec->decode) {
+          std::vector<int32_t> context;  // tokens each request holds in the cache before this step
+          for (int64_t id : batch) context.push_back((int32_t)(req[(size_t)id].input_len + req[(size_t)id].generated - 1));
+          if (exec->decode(exec->user, i, batch.data(), context.data(), (int32_t)batch.size()) != 0) return abort_run();
+        }
         std::vector<int64_t> gone;
         for (int64_t id : batch) {
           Request& r = req[(size_t)id];
@@ -276,6 +299,10 @@ struct Simulation {
         res.peak_kv_tokens = std::max(res.peak_kv_tokens, kv);
         std::unordered_set<int64_t> gone_set(gone.begin(), gone.end());
         for (int64_t id : gone) kv -= req[(size_t)id].input_len + req[(size_t)id].generated;
+        if (exec && exec->release && !gone.empty() &&
+            exec->release(exec->user, gone.data(), (int32_t)gone.size(), 0) != 0)
+          return abort_run();
+        const size_t n_finished = gone.size();
         // memory overflow: the most recently admitted request of this batch is recomputed later
         for (size_t k = batch.size(); kv > cfg.kv_capacity && k-- > 0;) {
           const int64_t id = batch[k];
@@ -291,6 +318,9 @@ struct Simulation {
           gone_set.insert(id);
           ++res.recomputes;
         }
+        if (exec && exec->release && gone.size() > n_finished &&
+            exec->release(exec->user, gone.data() + n_finished, (int32_t)(gone.size() - n_finished), 1) != 0)
+          return abort_run();
         if (!gone_set.empty()) remove_running(gone_set);
         if (cfg.work_stealing) {
           ws.on_return(i, gone.data(), (int)gone.size());
@@ -425,10 +455,11 @@ int tdp_switch_to_prefill(const double* x, const double* ms, int32_t n, double b
   return s < t ? 1 : 0;
 }
 
-int tdp_simulate(const tdp_sim_config* cfg, const int32_t* input_len, const int32_t* output_len,
-                 const int32_t* predict_len, int64_t n_requests, const double* decode_x, const double* decode_ms,
-                 int32_t n_decode, const double* prefill_x, const double* prefill_ms, int32_t n_prefill,
-                 tdp_sim_result* result, tdp_sim_event* events, int64_t events_cap) {
+int tdp_simulate_exec(const tdp_sim_config* cfg, const int32_t* input_len, const int32_t* output_len,
+                      const int32_t* predict_len, int64_t n_requests, const double* decode_x, const double* decode_ms,
+                      int32_t n_decode, const double* prefill_x, const double* prefill_ms, int32_t n_prefill,
+                      tdp_sim_result* result, tdp_sim_event* events, int64_t events_cap,
+                      const tdp_sim_executor* exec) {
   if (!cfg || !result || n_requests < 0 || (n_requests > 0 && (!input_len || !output_len || !predict_len)) ||
       events_cap < 0 || (events_cap > 0 && !events))
     return TDP_SCHED_EINVAL;
@@ -437,15 +468,24 @@ int tdp_simulate(const tdp_sim_config* cfg, const int32_t* input_len, const int3
   if (!sim.dec.ok() || !sim.pre.ok()) return TDP_SCHED_EINVAL;
   sim.events = events;
   sim.events_cap = events_cap;
+  sim.exec = exec;
   sim.req.resize((size_t)n_requests);
   for (int64_t i = 0; i < n_requests; ++i) {
     if (input_len[i] < 1 || output_len[i] < 1 || predict_len[i] < 0) return TDP_SCHED_EINVAL;
     sim.req[(size_t)i] = Request{input_len[i], output_len[i], predict_len[i], 0};
     sim.waiting.push_back(i);
   }
-  if (!sim.run()) return TDP_SCHED_EINVAL;
+  if (!sim.run()) return sim.aborted ? TDP_SCHED_EABORT : TDP_SCHED_EINVAL;
   *result = sim.res;
   return 0;
+}
+
+int tdp_simulate(const tdp_sim_config* cfg, const int32_t* input_len, const int32_t* output_len,
+                 const int32_t* predict_len, int64_t n_requests, const double* decode_x, const double* decode_ms,
+                 int32_t n_decode, const double* prefill_x, const double* prefill_ms, int32_t n_prefill,
+                 tdp_sim_result* result, tdp_sim_event* events, int64_t events_cap) {
+  return tdp_simulate_exec(cfg, input_len, output_len, predict_len, n_requests, decode_x, decode_ms, n_decode,
+                           prefill_x, prefill_ms, n_prefill, result, events, events_cap, nullptr);
 }
 
 }  // extern "C"

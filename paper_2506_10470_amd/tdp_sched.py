@@ -13,7 +13,7 @@ if not os.path.exists(LIB_PATH):
     raise ImportError("libtdp_sched.so is not built: run `python -m paper_2506_10470_amd.build`")
 lib = C.CDLL(LIB_PATH)
 
-EINVAL = -1
+EINVAL, EABORT = -1, -2
 EVENT_KINDS = ("prefill", "decode", "switch_to_prefill")
 
 
@@ -35,6 +35,15 @@ class SimEvent(C.Structure):
 
 _vp, _i32, _i64, _dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_double
 _pi32, _pi64, _pd = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_double)
+
+PREFILL_FN = C.CFUNCTYPE(C.c_int, _vp, _pi64, _pi32, _i32)
+DECODE_FN = C.CFUNCTYPE(C.c_int, _vp, _i32, _pi64, _pi32, _i32)
+RELEASE_FN = C.CFUNCTYPE(C.c_int, _vp, _pi64, _i32, _i32)
+
+
+class SimExecutor(C.Structure):
+    _fields_ = [("user", _vp), ("prefill", PREFILL_FN), ("decode", DECODE_FN), ("release", RELEASE_FN)]
+
 _SIGS = {
     "tdp_sched_abi_version": (C.c_int, []),
     "tdp_prefill_switch_create": (C.c_int, [_i64, _pi32, _i32, C.POINTER(_vp)]),
@@ -54,6 +63,8 @@ _SIGS = {
     "tdp_switch_to_prefill": (C.c_int, [_pd, _pd, _i32, _dbl, _pd, _i32, _dbl, _i32, _i32]),
     "tdp_simulate": (C.c_int, [C.POINTER(SimConfig), _pi32, _pi32, _pi32, _i64, _pd, _pd, _i32, _pd, _pd, _i32,
                                C.POINTER(SimResult), C.POINTER(SimEvent), _i64]),
+    "tdp_simulate_exec": (C.c_int, [C.POINTER(SimConfig), _pi32, _pi32, _pi32, _i64, _pd, _pd, _i32, _pd, _pd, _i32,
+                                    C.POINTER(SimResult), C.POINTER(SimEvent), _i64, C.POINTER(SimExecutor)]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
@@ -66,6 +77,8 @@ class SchedError(RuntimeError):
 
 
 def _check(rc: int) -> int:
+    if rc == EABORT:
+        raise SchedError("tdp_sched: the run was stopped by an executor callback")
     if rc < 0:
         raise SchedError("tdp_sched: invalid argument")
     return rc
@@ -188,5 +201,43 @@ def tdp_simulate(cfg: SimConfig, requests: Sequence[Tuple[int, int, int]], decod
     ev = (SimEvent * max(events_cap, 1))()
     _check(lib.tdp_simulate(C.byref(cfg), ins, outs, preds, n, dx, dms, nd, px, pms, npre, C.byref(res),
                             ev if events_cap else None, events_cap))
+    k = min(res.n_events, events_cap)
+    return res, [(EVENT_KINDS[ev[i].kind], ev[i].time_ms, ev[i].a, ev[i].b) for i in range(k)]
+
+
+def tdp_simulate_exec(cfg: SimConfig, requests: Sequence[Tuple[int, int, int]], decode_profile, prefill_profile,
+                      prefill=None, decode=None, release=None, events_cap: int = 0):
+    """tdp_simulate with the work done by the caller: `prefill(ids, input_lens)`, `decode(batch, ids, contexts)`
+    and `release(ids, reason)` are called with Python lists at the events they stand for (any may be None).
+    An exception raised in a callback stops the run and is raised again here."""
+    ins, n = _arr(C.c_int32, [r[0] for r in requests])
+    outs, _ = _arr(C.c_int32, [r[1] for r in requests])
+    preds, _ = _arr(C.c_int32, [r[2] for r in requests])
+    dx, dms, nd = _profile(decode_profile)
+    px, pms, npre = _profile(prefill_profile)
+    res = SimResult()
+    ev = (SimEvent * max(events_cap, 1))()
+    failure: List[BaseException] = []
+
+    def guard(fn, *args) -> int:
+        try:
+            fn(*args)
+            return 0
+        except BaseException as e:  # never let an exception cross the C frames
+            failure.append(e)
+            return 1
+
+    c_prefill = PREFILL_FN(lambda _u, ids, lens, k: guard(prefill, [ids[i] for i in range(k)], [lens[i] for i in range(k)])) \
+        if prefill else PREFILL_FN()
+    c_decode = DECODE_FN(lambda _u, b, ids, ctx, k: guard(decode, b, [ids[i] for i in range(k)], [ctx[i] for i in range(k)])) \
+        if decode else DECODE_FN()
+    c_release = RELEASE_FN(lambda _u, ids, k, why: guard(release, [ids[i] for i in range(k)], why)) \
+        if release else RELEASE_FN()
+    ex = SimExecutor(None, c_prefill, c_decode, c_release)
+    rc = lib.tdp_simulate_exec(C.byref(cfg), ins, outs, preds, n, dx, dms, nd, px, pms, npre, C.byref(res),
+                               ev if events_cap else None, events_cap, C.byref(ex))
+    if failure:
+        raise failure[0]
+    _check(rc)
     k = min(res.n_events, events_cap)
     return res, [(EVENT_KINDS[ev[i].kind], ev[i].time_ms, ev[i].a, ev[i].b) for i in range(k)]
