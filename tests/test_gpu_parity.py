@@ -389,3 +389,39 @@ def test_decode_every_span_length(tdp, span, monkeypatch):
     ctx = sorted({0, 31, span - 2, span - 1, span, span + 1, 2 * span - 1, 2 * span, 2 * span + 33,
                   min(3 * span + 7, 4096)} & set(range(0, 4097)))
     run_decode_case(tdp, "tiny_gqa", ctx, n_layers=1, max_pages_per_seq=4096 // 16 + 1)
+
+
+def test_decode_step_replays_from_a_hip_graph(tdp):
+    """A serving loop would capture the decode step once and replay it: the call only enqueues
+    kernels on the stream it is given (no allocation, no synchronisation, no memset node), so it
+    can be recorded into a HIP graph.  Three replays, with eager work and synchronisations between
+    them, must each reproduce the eager result bit for bit."""
+    sh = W.SHAPES["tiny_gqa"]
+    ctx = np.array([5, 40, 300, 77, 16, 255], dtype=np.int64)
+    batch = W.make_decode_batch(ctx)
+    B = len(ctx)
+    with Stage(tdp, sh, batch.num_pages, B, 0, 0, batch.tables.shape[1]) as st:
+        st.poison()
+        import_kv(tdp, st, ctx, batch.tables, 9)
+        x = W.hidden_states(sh, B, 9, device="cuda")
+        ctx_d, tab_d = i32(ctx), i32(batch.tables)
+        eager = torch.empty_like(x)
+        tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, B, eager)        # also warms every plan up
+        torch.cuda.synchronize()
+        out = torch.zeros_like(x)
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, B, out, torch.cuda.current_stream())
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for rep in range(3):
+            out.zero_()
+            scratch = torch.randn(1 << 16, device="cuda").sum()       # unrelated eager work in between
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), rep
+            del scratch
