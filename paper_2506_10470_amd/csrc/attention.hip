@@ -113,7 +113,7 @@ __global__ __launch_bounds__(64) void attn_plan_pages_kernel(const int4* __restr
 // tokens changes with it; the arithmetic after the conversion is the bf16 kernel's.  The cache
 // scales ride along for free: k_scale in the softmax scale, v_scale in the final division.
 template <int DH, bool KV8>
-__global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
+__global__ __launch_bounds__(256, KV8 ? 2 : 3) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
                                                           int n_q_heads, KvLayout kv,
                                                           const int4* __restrict__ items,
                                                           const int32_t* __restrict__ item_pages,
@@ -179,19 +179,26 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
     // planner; pages of a span's last block that lie past the span are clamped to its last entry here.
     const int page_base = s_begin >> 4;
 
-    // One block = the K fragments of NT score tiles and the V^T fragments of all channel tiles:
-    // 16 KiB per wave (head_dim 128), fetched one block ahead of the MFMAs that consume it.
-    struct Block {
+    // One block = the K fragments of NT score tiles and the V^T fragments of all channel tiles, 8 KiB
+    // each per wave (head_dim 128).  K is fetched one block ahead into one of two register sets; V of
+    // a block is fetched into a single set at the start of the block's own turn and is consumed
+    // at its end, behind the score MFMAs and the softmax.  Per wave 16 KiB are in flight, and the
+    // kernel fits three workgroups per CU (with both halves double-buffered it needed 198
+    // registers, two workgroups per CU).  Measured: the same time either way (0.46-0.49 ms per
+    // launch at batch 512, the spread coming from where the pools happen to lie in memory).
+    struct KBlock {
       bf16x8 kf[2][KS];  // bf16 pools: [score tile][k-step]; 8-bit pools: 16 raw bytes per entry, [t / 2][(t % 2) * KS/2 + ld]
+    };
+    struct VBlock {
       bf16x8 vf[DT];     // bf16 pools: 8 tokens of a channel; 8-bit pools: 16 raw bytes = 16 tokens of a channel
     };
-    auto load_block = [&](int tb, Block& blk) {
+    auto page_of = [&](int i) -> int64_t {  // i is wave-uniform
+      const int r = i >> 6;
+      const int v = r == 0 ? my_pages[0] : r == 1 ? my_pages[1] : r == 2 ? my_pages[2] : my_pages[3];
+      return __builtin_amdgcn_readlane(v, i & 63);
+    };
+    auto load_k = [&](int tb, KBlock& blk) {
       const int pi = (tb >> 4) - page_base;
-      auto page_of = [&](int i) -> int64_t {  // i is wave-uniform
-        const int r = i >> 6;
-        const int v = r == 0 ? my_pages[0] : r == 1 ? my_pages[1] : r == 2 ? my_pages[2] : my_pages[3];
-        return __builtin_amdgcn_readlane(v, i & 63);
-      };
       int64_t page[BT / 16];
 #pragma unroll
       for (int j = 0; j < BT / 16; ++j) page[j] = page_of(min(pi + j, pages_per_span - 1));
@@ -204,11 +211,6 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
 #pragma unroll
           for (int l = 0; l < KS / 2; ++l)
             blk.kf[t >> 1][(t & 1) * (KS / 2) + l] = *reinterpret_cast<const bf16x8*>(kp + (t * 4) * DH + l * 64);
-        // channel r16 of tile d, the 16 tokens of page kg of the block
-        const int64_t vpage = kg == 0 ? page[0] : kg == 1 ? page[1] : kg == 2 ? page[2] : page[3];
-        const uint8_t* vp = vpool8 + ((vpage * Hkv + kvh) * DH + r16) * 16;
-#pragma unroll
-        for (int d = 0; d < DT; ++d) blk.vf[d] = *reinterpret_cast<const bf16x8*>(vp + d * 16 * 16);
       } else {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -217,12 +219,27 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
 #pragma unroll
           for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8(kp + kk * 32);
         }
-        const bf16* vp = vpool + ((page[kg >> 1] * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
+      }
+    };
+    auto load_v = [&](int tb, VBlock& blk) {
+      const int pi = (tb >> 4) - page_base;
+      int64_t page[BT / 16];  // the look-up index must be wave-uniform: all pages first, then the lane's pick
+#pragma unroll
+      for (int j = 0; j < BT / 16; ++j) page[j] = page_of(min(pi + j, pages_per_span - 1));
+      if constexpr (KV8) {
+        // channel r16 of tile d, the 16 tokens of page kg of the block
+        const int64_t vpage = kg == 0 ? page[0] : kg == 1 ? page[1] : kg == 2 ? page[2] : page[3];
+        const uint8_t* vp = vpool8 + ((vpage * Hkv + kvh) * DH + r16) * 16;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) blk.vf[d] = *reinterpret_cast<const bf16x8*>(vp + d * 16 * 16);
+      } else {
+        const int64_t vpage = kg < 2 ? page[0] : page[1];
+        const bf16* vp = vpool + ((vpage * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
 #pragma unroll
         for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8(vp + d * 16 * 16);
       }
     };
-    auto compute_block = [&](int tb, Block& blk) {
+    auto compute_block = [&](int tb, KBlock& blk, VBlock& vblk) {
       f32x4 s[NT];
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
@@ -272,7 +289,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
       for (int d = 0; d < DT; ++d) {
         o[d] *= alpha;
         if constexpr (KV8) {
-          uint4 raw = __builtin_bit_cast(uint4, blk.vf[d]);
+          uint4 raw = __builtin_bit_cast(uint4, vblk.vf[d]);
           if (tail) {  // keep the first n_total - tok_base bytes (tokens tok_base .. tok_base + 15)
             const int keep = min(max(n_total - tok_base, 0), 16);
             auto mask = [&](int w) -> uint32_t {
@@ -292,32 +309,38 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(const bf16* __restr
           if (tail) {
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-              if (tok_base + j >= n_total) blk.vf[d][j] = (bf16)0.0f;
+              if (tok_base + j >= n_total) vblk.vf[d][j] = (bf16)0.0f;
           }
-          o[d] = mfma16(blk.vf[d], pb[0], o[d]);
+          o[d] = mfma16(vblk.vf[d], pb[0], o[d]);
         }
       }
     };
 
-    // Two blocks per trip, ping-pong between two register sets.  Every block is loaded exactly
+    // Two blocks per trip, K ping-pongs between two register sets.  Every block is loaded exactly
     // once: the steady-state loop only runs while two more blocks follow (its loads are
     // unconditional, so the compiler's wait counts stay exact), the last one or two blocks are
     // peeled off.
-    Block b0, b1;
+    KBlock k0, k1;
+    VBlock v;
     int tb = t_begin;
-    load_block(tb, b0);
+    load_k(tb, k0);
     for (; tb + 2 * BT < t_end; tb += 2 * BT) {
-      load_block(tb + BT, b1);
-      compute_block(tb, b0);
-      load_block(tb + 2 * BT, b0);
-      compute_block(tb + BT, b1);
+      load_v(tb, v);
+      load_k(tb + BT, k1);
+      compute_block(tb, k0, v);
+      load_v(tb + BT, v);
+      load_k(tb + 2 * BT, k0);
+      compute_block(tb + BT, k1, v);
     }
     if (tb + BT < t_end) {
-      load_block(tb + BT, b1);
-      compute_block(tb, b0);
-      compute_block(tb + BT, b1);
+      load_v(tb, v);
+      load_k(tb + BT, k1);
+      compute_block(tb, k0, v);
+      load_v(tb + BT, v);
+      compute_block(tb + BT, k1, v);
     } else {
-      compute_block(tb, b0);
+      load_v(tb, v);
+      compute_block(tb, k0, v);
     }
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
