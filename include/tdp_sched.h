@@ -92,7 +92,11 @@ TDP_SCHED_API int tdp_switch_to_prefill(const double* x, const double* ms, int32
  * the decode phase runs n_stages batches with or without work stealing and ends by the intensity
  * rule (intensity_switch = 0: when every running request is done).  A request that does not fit
  * any more during decode is recomputed later (its generated tokens join its prompt).
- * Events, in order of occurrence: kind 0 = prefill batch left the pipeline (a = requests, b =
+ * Phase switches are compact (Sec. 3.1): after a switch to prefill is decided the prefill batches enter stage 0
+ * behind the decode steps still in flight (the bubble is the mismatch of step times, Sec. 3.5), and a decode
+ * batch starts as soon as stage 0 is free and each of its requests has the token its prefill produced.
+ * Events, in the order the scheduler handles them (times are not monotone across a switch to prefill, where
+ * the steps in flight return while the first prefills are under way): kind 0 = prefill batch left the pipeline (a = requests, b =
  * tokens), 1 = decode batch returned (a = batch index, b = size it is resubmitted with), 2 = switch
  * to prefill decided (a = batch size, b = pending prefill batches).  At most events_cap events are
  * written; result->n_events is the number that occurred. */

@@ -261,6 +261,7 @@ def simulate(requests: Sequence[Tuple[int, int, int]], cfg: SimConfig, decode_pr
         return sum(r.input_len + r.generated for r in running)
 
     now = 0.0
+    ready_at: Dict[int, float] = {}  # when a request's newest token became available (its prefill left the pipeline)
     while waiting or running:
         # ---------------- prefill phase
         plan = plan_prefill(waiting, running, cfg)
@@ -276,6 +277,7 @@ def simulate(requests: Sequence[Tuple[int, int, int]], cfg: SimConfig, decode_pr
                 r.generated = 1  # the prefill produces the first output token
                 res.generated_tokens += 1
                 running.append(r)
+                ready_at[r.rid] = finish
             taken += len(batch)
             last_finish = max(last_finish, finish)
         del waiting[:taken]
@@ -288,16 +290,18 @@ def simulate(requests: Sequence[Tuple[int, int, int]], cfg: SimConfig, decode_pr
             now = last_finish
             continue
         res.phase_switches += 1
-        # ---------------- decode phase: starts once the last prefill has left the pipeline (a
-        # request's first decode step needs the token its prefill produced)
-        now = last_finish
+        # ---------------- decode phase, entered compactly (Sec. 3.1: phase switches leave minimal
+        # bubbles): a batch starts as soon as stage 0 is free and every request in it has the token its
+        # prefill produced, so the batches of older requests follow the last prefills through the pipeline
         ws = WorkStealing(n, [r.rid for r in running])
         compositions = [list(b) for b in ws.batches]
         returns: List[Tuple[float, int]] = []  # (return time, batch) of the steps in flight
         for i in range(n):
             if compositions[i]:
-                returns.append((run_batch(max(now, stage_free[0]), interp_time(decode_profile, len(compositions[i]))), i))
+                ready = max([now] + [ready_at.get(rid, 0.0) for rid in compositions[i]])
+                returns.append((run_batch(max(ready, stage_free[0]), interp_time(decode_profile, len(compositions[i]))), i))
         draining = False
+        t_switch = 0.0
         while returns:
             returns.sort()
             t_ret, i = returns.pop(0)
@@ -343,6 +347,7 @@ def simulate(requests: Sequence[Tuple[int, int, int]], cfg: SimConfig, decode_pr
                 if pend_ms and size > 0 and switch_to_prefill(decode_profile, size, pend_ms, step_ms, n,
                                                                cfg.count_decode_steps):
                     draining = True  # the steps in flight come back, nothing is resubmitted
+                    t_switch = t_ret
                     res.events.append(("switch_to_prefill", t_ret, size, len(pend_ms)))
                     continue
             if compositions[i]:
@@ -357,6 +362,9 @@ def simulate(requests: Sequence[Tuple[int, int, int]], cfg: SimConfig, decode_pr
                             returns.append((run_batch(t_ret, interp_time(decode_profile, len(compositions[k]))), k))
         if draining:
             res.phase_switches += 1
+            # the prefills enter stage 0 behind the steps still in flight instead of waiting for them to
+            # return: the bubble of the switch is the mismatch of step times (Sec. 3.5), not a drained pipeline
+            now = t_switch
         # every request still alive (in a batch or withheld) is carried into the next phase
     res.total_ms = max(stage_free)
     return res

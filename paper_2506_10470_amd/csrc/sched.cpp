@@ -143,6 +143,7 @@ struct Simulation {
   std::deque<int64_t> waiting;     // request ids, first come first served
   std::vector<int64_t> running;    // live requests in admission order
   std::vector<double> stage_free;
+  std::vector<double> ready_at;    // per request: when its newest token became available (its prefill left the pipeline)
   int64_t kv = 0;                  // tokens held by the running requests
   tdp_sim_result res{};
   tdp_sim_event* events = nullptr;
@@ -235,6 +236,7 @@ struct Simulation {
           ++res.generated_tokens;
           kv += r.input_len + 1;
           running.push_back(id);
+          ready_at[(size_t)id] = finish;
           ids.push_back(id);
           lens.push_back((int32_t)r.input_len);
         }
@@ -263,16 +265,21 @@ struct Simulation {
         continue;
       }
       ++res.phase_switches;
-      // ---- decode phase: starts once the last prefill has left the pipeline
-      now = last_finish;
+      // ---- decode phase, entered compactly (Sec. 3.1: phase switches leave minimal bubbles): a batch
+      // starts as soon as stage 0 is free and every request in it has the token its prefill produced
       tdp_work_stealing ws = make_stealing(n, running.data(), (int64_t)running.size());
       std::vector<double> return_at((size_t)n, -1.0);  // < 0: not in flight
       auto launch = [&](int i, double ready) {
         return_at[(size_t)i] = run_batch(ready, dec.time((double)ws.batches[(size_t)i].size()));
       };
       for (int i = 0; i < n; ++i)
-        if (!ws.batches[(size_t)i].empty()) launch(i, std::max(now, stage_free[0]));
+        if (!ws.batches[(size_t)i].empty()) {
+          double ready = now;
+          for (int64_t id : ws.batches[(size_t)i]) ready = std::max(ready, ready_at[(size_t)id]);
+          launch(i, std::max(ready, stage_free[0]));
+        }
       bool draining = false;
+      double t_switch = 0.0;
       for (;;) {
         int i = -1;
         for (int k = 0; k < n; ++k)
@@ -338,6 +345,7 @@ struct Simulation {
             if (dec.spatial((double)batch.size()) <
                 temporal(pend_ms.data(), (int)pend_ms.size(), step_ms, n, cfg.count_decode_steps != 0)) {
               draining = true;  // the steps in flight come back, nothing is resubmitted
+              t_switch = t_ret;
               event(2, t_ret, (int64_t)batch.size(), (int64_t)pend_ms.size());
               continue;
             }
@@ -355,7 +363,12 @@ struct Simulation {
             }
         }
       }
-      if (draining) ++res.phase_switches;
+      if (draining) {
+        ++res.phase_switches;
+        // the prefills enter stage 0 behind the steps still in flight instead of waiting for them to return:
+        // the bubble of the switch is the mismatch of step times (Sec. 3.5), not a drained pipeline
+        now = t_switch;
+      }
     }
     res.total_ms = *std::max_element(stage_free.begin(), stage_free.end());
     return true;
@@ -470,6 +483,7 @@ int tdp_simulate_exec(const tdp_sim_config* cfg, const int32_t* input_len, const
   sim.events_cap = events_cap;
   sim.exec = exec;
   sim.req.resize((size_t)n_requests);
+  sim.ready_at.assign((size_t)n_requests, 0.0);
   for (int64_t i = 0; i < n_requests; ++i) {
     if (input_len[i] < 1 || output_len[i] < 1 || predict_len[i] < 0) return TDP_SCHED_EINVAL;
     sim.req[(size_t)i] = Request{input_len[i], output_len[i], predict_len[i], 0};

@@ -195,6 +195,51 @@ def test_single_stage_single_request_timeline():
     assert S.bubble_ratio(res, 1) == pytest.approx(0.0)
 
 
+def test_two_stage_timeline_by_hand_phase_switches_are_compact():
+    """Two stages, two prompts that need a prefill batch each (p = 10 ms per stage), decode steps of
+    d = 2 ms per stage, three output tokens per request.  By hand: the prefills leave the pipeline at
+    2p = 20 and 3p = 30.  Decode batch 0 (the first request, whose token exists at 20) does not wait
+    for the second prefill to leave: it enters stage 0 at 20, finds stage 1 busy until 30 and returns
+    at 30 + d = 32; batch 1 (ready at 30) follows it: 34; their second steps return at 36 and 38.
+    (Waiting for the pipeline to drain first would give 34, 36, 38, 40.)"""
+    flat_decode = [(1, 2.0), (64, 2.0)]
+    flat_prefill = [(1, 10.0), (64, 10.0)]
+    cfg = S.SimConfig(n_stages=2, kv_capacity=10000, prefill_token_budget=8, intensity_switch=False)
+    res = S.simulate([(8, 3, 3), (8, 3, 3)], cfg, flat_decode, flat_prefill)
+    assert [(k, a, b) for k, _, a, b in res.events] == [("prefill", 1, 8), ("prefill", 1, 8), ("decode", 0, 1),
+                                                        ("decode", 1, 1), ("decode", 0, 0), ("decode", 1, 0)]
+    assert [t for _, t, _, _ in res.events] == pytest.approx([20.0, 30.0, 32.0, 34.0, 36.0, 38.0])
+    assert res.total_ms == pytest.approx(38.0)
+    # stage time used: 2 prefills + 4 decode steps on each of 2 stages
+    assert res.busy_ms == pytest.approx(2 * (2 * 10.0 + 4 * 2.0))
+
+
+def test_switch_to_prefill_does_not_wait_for_the_steps_in_flight():
+    """A decode phase that hands over to prefills: the first prefill enters stage 0 behind the decode
+    steps that are still in the pipeline, so it leaves the pipeline earlier than the last of them
+    plus a full pass would allow."""
+    rng = random.Random(11)
+    reqs = [(rng.randint(20, 60), rng.randint(2, 40), rng.randint(2, 40)) for _ in range(120)]
+    cfg = S.SimConfig(n_stages=4, kv_capacity=1500, prefill_token_budget=256)
+    res = S.simulate(reqs, cfg, PROFILE, PREFILL_PROFILE)
+    ev = res.events
+    switches = [i for i, e in enumerate(ev) if e[0] == "switch_to_prefill"]
+    assert switches, "the run must contain a switch for this pin to say anything"
+    compact = 0
+    for i in switches:
+        later_decodes = [e[1] for e in ev[i + 1:] if e[0] == "decode"]
+        first_prefill = next((e for e in ev[i + 1:] if e[0] == "prefill"), None)
+        if first_prefill is None or not later_decodes:
+            continue
+        tokens = first_prefill[3]
+        full_pass = 4 * S.interp_time(PREFILL_PROFILE, tokens)
+        # drained-first scheduling could not finish the prefill before (last in-flight return + 4 stage times)
+        last_inflight = max([t for k, t, _, _ in ev[i + 1: ev.index(first_prefill)] if k == "decode"] + [ev[i][1]])
+        if first_prefill[1] < last_inflight + full_pass - 1e-9:
+            compact += 1
+    assert compact > 0
+
+
 def test_work_stealing_does_not_hurt_a_skewed_decode_phase():
     """Batches that lose requests at different rates: stealing must not lengthen the run."""
     rng = random.Random(5)
