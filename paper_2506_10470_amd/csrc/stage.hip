@@ -164,10 +164,8 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
   // A projection whose K range was split leaves fp32 partials in the workspace; the kernel that
   // consumes its output sums them (RoPE for QKV, the following RMSNorm for the two residual
   // projections), which saves a reduce launch and one round trip of the result per projection.
-  // One workgroup per row does the summing, so the batch must be large enough to fill the chip that
-  // way: measured on the 70B-shaped stage, the fused form gains 1.6 % at 512 rows, is level at 128
-  // and 10 % slower than the separate, fully parallel reduce kernel at 32.
-  const bool fuse_reduce = M >= 192;
+  // (measured on the 70B-shaped stage with 1024 threads per row: +1.3 % at 16 rows, +1.7 % at 128, +1.6 % at 512)
+  const bool fuse_reduce = true;
   int down_splits = 1;  // > 1: x (this layer's input) still has to be formed from h + partials
   for (int l = l_begin; l < l_end; ++l) {
     const KvLayout kv = kv_layout(st, l);
