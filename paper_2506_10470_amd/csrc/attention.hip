@@ -113,7 +113,7 @@ __global__ __launch_bounds__(64) void attn_plan_pages_kernel(const int4* __restr
 // tokens changes with it; the arithmetic after the conversion is the bf16 kernel's.  The cache
 // scales ride along for free: k_scale in the softmax scale, v_scale in the final division.
 template <int DH, bool KV8>
-__global__ __launch_bounds__(256, KV8 ? 2 : 3) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
+__global__ __launch_bounds__(256, 3) void attn_decode_kernel(const bf16* __restrict__ qkv, int64_t ld,
                                                           int n_q_heads, KvLayout kv,
                                                           const int4* __restrict__ items,
                                                           const int32_t* __restrict__ item_pages,
