@@ -20,8 +20,10 @@
  *    from two streams at once: its scratch buffers are shared.
  *  - The caller owns page allocation: which physical page belongs to which request is the
  *    engine's business (Sec. 3.2.1).  The stage only writes the slot the tables name.
- *    Contents of device-side tables are trusted: a page id outside [0, num_pages) or a
- *    position beyond 16 * max_pages_per_seq is undefined behaviour.
+ *    Contents of device-side tables are trusted by the prefill / decode / import / export calls:
+ *    a page id outside [0, num_pages) or a position beyond 16 * max_pages_per_seq is undefined
+ *    behaviour there.  tdp_stage_check_decode / tdp_stage_check_prefill validate them first for a
+ *    caller that wants that (they cost a synchronisation, so they are not part of the hot calls).
  */
 #ifndef TDP_H_
 #define TDP_H_
@@ -175,6 +177,24 @@ TDP_API int tdp_stage_prefill(tdp_stage* st, const void* hidden_in, const int32_
  */
 TDP_API int tdp_stage_decode(tdp_stage* st, const void* hidden_in, const int32_t* ctx_lens,
                      const int32_t* block_tables, int32_t batch, void* hidden_out, void* stream);
+
+/*
+ * Validate the device-side tables of a decode or prefill call before making it.  Checked, for every
+ * row of the batch: the length (decode: 0 <= ctx_lens[b] and ctx_lens[b] + 1 <= 16 * max_pages_per_seq;
+ * prefill: 0 <= len_s <= 16 * max_pages_per_seq, cu_seqlens[0] = 0, cu_seqlens[n_seqs] = total_tokens);
+ * every table entry the call would use lies in [0, num_pages); and no page that the call writes
+ * (decode: the page of position ctx_lens[b]; prefill: every page of every prompt) appears a second
+ * time among the entries the call uses - two requests writing one page, or one reading what another
+ * writes, is how a page-allocation mistake shows (the engine owns allocation, Sec. 3.2.1).  Pages
+ * that are only read may be shared.  The kernels read the tables inside [rows][max_pages_per_seq]
+ * whatever the lengths say, so the check itself is safe on arbitrary input.
+ * Returns TDP_OK, or TDP_EINVAL with a message naming the first offending row and what is wrong
+ * with it.  Same size limits and pointer kinds as the call it guards.  Runs on `stream` and waits for it.
+ */
+TDP_API int tdp_stage_check_decode(tdp_stage* st, const int32_t* ctx_lens, const int32_t* block_tables,
+                                   int32_t batch, void* stream);
+TDP_API int tdp_stage_check_prefill(tdp_stage* st, const int32_t* cu_seqlens, const int32_t* block_tables,
+                                    int32_t n_seqs, int32_t total_tokens, void* stream);
 
 /*
  * Restrict the following prefill/decode calls to layers [first, first + count) of the stage, as

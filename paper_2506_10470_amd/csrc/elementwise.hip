@@ -417,6 +417,91 @@ hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float*
   return hipGetLastError();
 }
 
+// ---- optional validation of device-side tables ---------------------------------------------
+// The stage calls trust the tables they are given; these kernels are what a caller runs first when
+// it does not.  They read a table only at (row < n, entry < max_pages_per_seq), whatever the lengths
+// say, so they are safe on any input.  res[0] counts violations, res[1] keeps the smallest
+// row * 8 + kind among them.
+enum TableFault { kFaultLength = 1, kFaultPage = 2, kFaultShared = 3, kFaultPrefix = 4 };
+
+__device__ __forceinline__ void table_fault(int32_t* res, int row, int kind) {
+  atomicAdd(&res[0], 1);
+  atomicMin(&res[1], row * 8 + kind);
+}
+
+__global__ void table_check_init_kernel(int32_t* __restrict__ owner, int num_pages, int32_t* __restrict__ res) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < num_pages) owner[i] = -1;
+  if (i == 0) {
+    res[0] = 0;
+    res[1] = 0x7fffffff;
+  }
+}
+
+// tokens of row r after the call (decode: ctx + 1; prefill: the prompt's length), or -1 if the
+// length itself is invalid
+__device__ __forceinline__ int table_row_tokens(int decode, const int32_t* lens, int r, int max_pos) {
+  const int64_t n = decode ? (int64_t)lens[r] + 1 : (int64_t)lens[r + 1] - (int64_t)lens[r];
+  const int64_t lo = decode ? 1 : 0;
+  return (n < lo || n > max_pos) ? -1 : (int)n;
+}
+
+// pass 1: lengths, page ranges, and every page the call will WRITE is claimed by its row
+// (decode: the page of position ctx; prefill: every page of the prompt)
+__global__ __launch_bounds__(64) void table_check_claim_kernel(int decode, const int32_t* __restrict__ lens,
+                                                               const int32_t* __restrict__ tables, int n_rows,
+                                                               int max_pages_per_seq, int num_pages, int total_tokens,
+                                                               int32_t* __restrict__ owner, int32_t* __restrict__ res) {
+  const int r = blockIdx.x;
+  if (!decode && r == 0 && threadIdx.x == 0) {
+    if (lens[0] != 0) table_fault(res, 0, kFaultPrefix);
+    if (lens[n_rows] != total_tokens) table_fault(res, n_rows - 1, kFaultPrefix);
+  }
+  const int n = table_row_tokens(decode, lens, r, max_pages_per_seq * 16);
+  if (n < 0) {
+    if (threadIdx.x == 0) table_fault(res, r, kFaultLength);
+    return;
+  }
+  const int n_pages = (n + 15) / 16;
+  for (int j = threadIdx.x; j < n_pages; j += 64) {
+    const int p = tables[(int64_t)r * max_pages_per_seq + j];
+    if (p < 0 || p >= num_pages) {
+      table_fault(res, r, kFaultPage);
+      continue;
+    }
+    if (!decode || j == n_pages - 1) {
+      if (atomicCAS(&owner[p], -1, r) != -1) table_fault(res, r, kFaultShared);
+    }
+  }
+}
+
+// pass 2 (decode): no page that a row only reads is written by any row of the batch
+__global__ __launch_bounds__(64) void table_check_read_kernel(const int32_t* __restrict__ lens,
+                                                              const int32_t* __restrict__ tables,
+                                                              int max_pages_per_seq, int num_pages,
+                                                              const int32_t* __restrict__ owner,
+                                                              int32_t* __restrict__ res) {
+  const int r = blockIdx.x;
+  const int n = table_row_tokens(1, lens, r, max_pages_per_seq * 16);
+  if (n < 0) return;
+  const int n_pages = (n + 15) / 16;
+  for (int j = threadIdx.x; j < n_pages - 1; j += 64) {
+    const int p = tables[(int64_t)r * max_pages_per_seq + j];
+    if (p >= 0 && p < num_pages && owner[p] != -1) table_fault(res, r, kFaultShared);
+  }
+}
+
+hipError_t launch_table_check(int decode, const int32_t* lens, const int32_t* tables, int n_rows,
+                              int max_pages_per_seq, int num_pages, int total_tokens, int32_t* owner, int32_t* res,
+                              hipStream_t s) {
+  table_check_init_kernel<<<(num_pages + 255) / 256, 256, 0, s>>>(owner, num_pages, res);
+  table_check_claim_kernel<<<n_rows, 64, 0, s>>>(decode, lens, tables, n_rows, max_pages_per_seq, num_pages,
+                                                 total_tokens, owner, res);
+  if (decode)
+    table_check_read_kernel<<<n_rows, 64, 0, s>>>(lens, tables, max_pages_per_seq, num_pages, owner, res);
+  return hipGetLastError();
+}
+
 // ---- pipeline ends: row gather (token embedding; last-token selection), bf16 conversion, argmax ----
 
 // dst[m][:] = src[idx[m]][:]; one workgroup per row, 16-byte pieces.  An index outside

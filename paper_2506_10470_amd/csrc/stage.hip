@@ -57,6 +57,7 @@ struct tdp_stage {
   int32_t* attn_item_pages = nullptr;  // physical pages of every item's span
   int max_chunks = 0;             // spans of kDecodeSpanMin tokens in the longest context
   float2* rope_table = nullptr;
+  int32_t *check_owner = nullptr, *check_res = nullptr;  // scratch of the table checks
   int max_pos = 0;
   int maxM = 0;
   int layer_first = 0, layer_count = 0;  // count 0 = all layers
@@ -325,6 +326,8 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
     false);
   A(&st->attn_n_items, 1, true);
   A(&st->rope_table, (int64_t)st->max_pos * (dh / 2), false);
+  A(&st->check_owner, c.num_pages, false);
+  A(&st->check_res, 2, true);
   if (e == hipSuccess) {
     // (cos, sin)(pos * base^(-2i/dh)) in double precision, stored as fp32
     std::vector<float2> tab((size_t)st->max_pos * (dh / 2));
@@ -351,7 +354,8 @@ void tdp_stage_destroy(tdp_stage* st) {
   (void)hipDeviceSynchronize();
   void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->bqkv, st->kpool, st->vpool, st->y,
                   st->qkv, st->attn, st->h, st->u, st->xa, st->xb, st->ws, st->part_o, st->part_ml,
-                  st->attn_items, st->attn_n_items, st->attn_item_pages, st->rope_table};
+                  st->attn_items, st->attn_n_items, st->attn_item_pages, st->rope_table, st->check_owner,
+                  st->check_res};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
   for (hipEvent_t ev : st->ev_start) (void)hipEventDestroy(ev);
@@ -492,6 +496,45 @@ int tdp_stage_decode(tdp_stage* st, const void* hidden_in, const int32_t* ctx_le
   if (!hidden_in || !hidden_out || !ctx_lens || !block_tables) return fail(TDP_EINVAL, "null pointer");
   return run_layers(st, hidden_in, hidden_out, batch, ctx_lens, nullptr, batch, block_tables,
                     (hipStream_t)stream);
+}
+
+static int check_tables(tdp_stage* st, int decode, const int32_t* lens, const int32_t* block_tables, int n_rows,
+                        int total_tokens, hipStream_t s) {
+  HIP_TRY(launch_table_check(decode, lens, block_tables, n_rows, st->cfg.max_pages_per_seq, st->cfg.num_pages,
+                             total_tokens, st->check_owner, st->check_res, s));
+  int32_t res[2] = {0, 0};
+  HIP_TRY(hipMemcpyAsync(res, st->check_res, sizeof res, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  if (res[0] == 0) return TDP_OK;
+  const int row = res[1] / 8, kind = res[1] % 8;
+  static const char* const what[] = {
+      "", "length outside what a block-table row can hold", "page id outside [0, num_pages)",
+      "a page this call writes appears more than once in the batch", "cu_seqlens does not run from 0 to total_tokens"};
+  char buf[200];
+  snprintf(buf, sizeof buf, "%d table violation(s); first: row %d, %s", (int)res[0], row,
+           kind >= 1 && kind <= 4 ? what[kind] : "unknown");
+  return fail(TDP_EINVAL, buf);
+}
+
+int tdp_stage_check_decode(tdp_stage* st, const int32_t* ctx_lens, const int32_t* block_tables, int32_t batch,
+                           void* stream) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (batch < 0) return fail(TDP_EINVAL, "negative batch");
+  if (batch > st->cfg.max_batch) return fail(TDP_EINVAL, "batch exceeds max_batch");
+  if (batch == 0) return TDP_OK;
+  if (!ctx_lens || !block_tables) return fail(TDP_EINVAL, "null pointer");
+  return check_tables(st, 1, ctx_lens, block_tables, batch, 0, (hipStream_t)stream);
+}
+
+int tdp_stage_check_prefill(tdp_stage* st, const int32_t* cu_seqlens, const int32_t* block_tables, int32_t n_seqs,
+                            int32_t total_tokens, void* stream) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (n_seqs < 0 || total_tokens < 0) return fail(TDP_EINVAL, "negative size");
+  if (n_seqs > st->cfg.max_seqs) return fail(TDP_EINVAL, "n_seqs exceeds max_seqs");
+  if (total_tokens > st->cfg.max_tokens) return fail(TDP_EINVAL, "total_tokens exceeds max_tokens");
+  if (n_seqs == 0 || total_tokens == 0) return TDP_OK;
+  if (!cu_seqlens || !block_tables) return fail(TDP_EINVAL, "null pointer");
+  return check_tables(st, 0, cu_seqlens, block_tables, n_seqs, total_tokens, (hipStream_t)stream);
 }
 
 int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out, int32_t M, int32_t N, int32_t K,

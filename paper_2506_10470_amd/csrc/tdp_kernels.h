@@ -114,6 +114,13 @@ hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const Kv
                           const int32_t* cu_seqlens, int n_seqs, int total_tokens,
                           const int32_t* block_tables, int max_pages_per_seq, hipStream_t s);
 
+// Validation of the tables of a decode (lens = ctx_lens[n_rows]) or prefill (lens = cu_seqlens[n_rows + 1])
+// call.  owner: scratch int32[num_pages]; res: int32[2] = {violations, min(row * 8 + kind)} with kind
+// 1 = length, 2 = page id, 3 = written page shared, 4 = cu_seqlens ends.  Reads the tables in bounds on any input.
+hipError_t launch_table_check(int decode, const int32_t* lens, const int32_t* tables, int n_rows,
+                              int max_pages_per_seq, int num_pages, int total_tokens, int32_t* owner, int32_t* res,
+                              hipStream_t s);
+
 // ---- attention -------------------------------------------------------------------------------
 // tokens of one request's context handled by one workgroup (multiples of 128: four waves, 32-token blocks)
 constexpr int kDecodeSpanMin = 256, kDecodeSpanMax = 4096;

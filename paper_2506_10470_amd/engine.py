@@ -27,13 +27,17 @@ class StageWorker:
     (tdp_ends) that the caller created and loaded.  `prompts[i]` are request i's prompt token ids."""
 
     def __init__(self, tdp, stage: int, ends: int, d_model: int, num_pages: int, max_pages_per_seq: int,
-                 max_batch: int, max_tokens: int, max_seqs: int, prompts: Sequence[Sequence[int]], stream=None):
+                 max_batch: int, max_tokens: int, max_seqs: int, prompts: Sequence[Sequence[int]], stream=None,
+                 check_tables: bool = False):
+        """check_tables: validate every call's block tables on the GPU first (tdp_stage_check_*): one
+        synchronisation per call, for runs that test the allocator rather than the throughput."""
         self.tdp, self.stage, self.ends = tdp, stage, ends
         self.d_model = d_model
         self.max_pps, self.max_batch, self.max_tokens, self.max_seqs = max_pages_per_seq, max_batch, max_tokens, max_seqs
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         self.free_pages: List[int] = list(range(num_pages - 1, -1, -1))
         self.num_pages = num_pages
+        self.check_tables = check_tables
         self.pages: Dict[int, List[int]] = {}
         self.prompts = [list(map(int, p)) for p in prompts]
         self.generated: List[List[int]] = [[] for _ in prompts]
@@ -83,8 +87,11 @@ class StageWorker:
         cu[1:] = np.cumsum(lens)
         tdp = self.tdp
         x, y = self.hidden[:total], self.hidden_out[:total]
+        cu_dev, table = self._i32(cu), self._table(ids)
+        if self.check_tables:
+            tdp.tdp_stage_check_prefill(self.stage, cu_dev, table, n, total, self.stream)
         tdp.tdp_embed_tokens(self.ends, self._i32(toks), total, x, self.stream)
-        tdp.tdp_stage_prefill(self.stage, x, self._i32(cu), self._table(ids), n, total, y, self.stream)
+        tdp.tdp_stage_prefill(self.stage, x, cu_dev, table, n, total, y, self.stream)
         tdp.tdp_lm_head(self.ends, y, total, self._i32(cu[1:] - 1), n, None, self.next_tok[:n], self.stream)
         for rid, t in zip(ids, self.next_tok[:n].cpu().tolist()):
             self.generated[rid].append(int(t))
@@ -107,8 +114,11 @@ class StageWorker:
                 self.pages[rid] += self._take(1)
         tdp = self.tdp
         x, y = self.hidden[:n], self.hidden_out[:n]
+        ctx_dev, table = self._i32(contexts), self._table(ids)
+        if self.check_tables:
+            tdp.tdp_stage_check_decode(self.stage, ctx_dev, table, n, self.stream)
         tdp.tdp_embed_tokens(self.ends, self._i32([self.generated[rid][-1] for rid in ids]), n, x, self.stream)
-        tdp.tdp_stage_decode(self.stage, x, self._i32(contexts), self._table(ids), n, y, self.stream)
+        tdp.tdp_stage_decode(self.stage, x, ctx_dev, table, n, y, self.stream)
         tdp.tdp_lm_head(self.ends, y, n, None, n, None, self.next_tok[:n], self.stream)
         for rid, t in zip(ids, self.next_tok[:n].cpu().tolist()):
             self.generated[rid].append(int(t))

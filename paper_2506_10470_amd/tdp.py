@@ -65,6 +65,8 @@ _SIGS = {
     "tdp_stage_kv_export": (C.c_int, [_vp, _i32, _vp, _vp, _vp, _vp, _i32, _i32, _vp]),
     "tdp_stage_prefill": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "tdp_stage_decode": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "tdp_stage_check_decode": (C.c_int, [_vp, _vp, _vp, _i32, _vp]),
+    "tdp_stage_check_prefill": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "tdp_stage_set_layer_range": (C.c_int, [_vp, _i32, _i32]),
     "tdp_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "tdp_e4m3_from_f32": (C.c_int, [_vp, _vp, _i64, C.c_float, _vp]),
@@ -155,6 +157,15 @@ def tdp_stage_prefill(st, hidden_in, cu_seqlens, block_tables, n_seqs, total_tok
 def tdp_stage_decode(st, hidden_in, ctx_lens, block_tables, batch, hidden_out, stream=None) -> None:
     _check(lib.tdp_stage_decode(st, _ptr(hidden_in), _ptr(ctx_lens), _ptr(block_tables), batch,
                                 _ptr(hidden_out), _stream(stream)))
+
+
+def tdp_stage_check_decode(st, ctx_lens, block_tables, batch, stream=None) -> None:
+    _check(lib.tdp_stage_check_decode(st, _ptr(ctx_lens), _ptr(block_tables), batch, _stream(stream)))
+
+
+def tdp_stage_check_prefill(st, cu_seqlens, block_tables, n_seqs, total_tokens, stream=None) -> None:
+    _check(lib.tdp_stage_check_prefill(st, _ptr(cu_seqlens), _ptr(block_tables), n_seqs, total_tokens,
+                                       _stream(stream)))
 
 
 def tdp_stage_set_layer_range(st, first: int, count: int) -> None:

@@ -80,6 +80,8 @@ def test_layer_range_and_timing_calls_reject_null_stage():
     assert tdp.lib.tdp_stage_timing_enable(None, 1) == tdp.EINVAL
     assert tdp.lib.tdp_stage_kv_import(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL
     assert tdp.lib.tdp_stage_kv_export(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_check_decode(None, None, None, 1, None) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_check_prefill(None, None, None, 1, 1, None) == tdp.EINVAL
 
 
 def test_ends_entry_points_reject_bad_arguments():

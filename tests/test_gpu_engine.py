@@ -37,7 +37,7 @@ def make_requests(n, seed):
     return reqs, prompts
 
 
-def run_engine(sh, reqs, prompts, n_stages, capacity, budget=128):
+def run_engine(sh, reqs, prompts, n_stages, capacity, budget=128, check_tables=True):
     max_len = max(r[0] + r[1] for r in reqs) + 1
     max_pps = (max_len + 15) // 16 + 1
     num_pages = (capacity + 15) // 16 + len(reqs)
@@ -45,7 +45,7 @@ def run_engine(sh, reqs, prompts, n_stages, capacity, budget=128):
             Ends(sh, VOCAB, max(budget, max_len, len(reqs))) as ends:
         st.poison()
         w = StageWorker(tdp, st.h, ends.h, sh.d_model, num_pages, max_pps, len(reqs), max(budget, max_len), len(reqs),
-                        prompts)
+                        prompts, check_tables=check_tables)   # every call's tables are validated on the GPU first
         cfg = L.SimConfig(n_stages, capacity, budget, 1, 1, 1, 1)
         res, ev = w.run(L, cfg, reqs, DEC, PRE, events_cap=1 << 20)
         torch.cuda.synchronize()
