@@ -227,6 +227,28 @@ def fp8_kv_section(tdp, W, Stage, A, shape, sargs, dec_ctx, i32, steps, warmup):
             "attention": kern.get("attention"), "sweep": sweep}
 
 
+def empirical_section(tdp, st, n_layers, stream):
+    """What this GPU sustains with nothing else in the way (library probes, HIP events inside the calls):
+    HBM reads over a footprint like one decode-attention launch's (2 GiB) in address order and in scattered
+    4 KiB pieces (how a paged cache is read), the in-order rate over a large footprint, and a register-only
+    bf16 MFMA loop.  Context for the published peaks the roofline fractions are quoted against."""
+    k, _, n = tdp.tdp_stage_kv_pool(st.h, 0)
+    total = n * n_layers                              # the layers' K pools are one contiguous allocation
+    out = {}
+    for name, size, scattered in (("hbm_read_in_order_gbs", 2 << 30, False),
+                                  ("hbm_read_4k_scattered_gbs", 2 << 30, True),
+                                  ("hbm_read_in_order_large_gbs", 16 << 30, False),
+                                  ("hbm_read_4k_scattered_large_gbs", 16 << 30, True)):
+        nbytes, ms = tdp.tdp_probe_hbm_read(k, min(size, total), scattered, 5, stream)
+        out[name] = round(nbytes / ms / 1e6, 1)
+        out[name.replace("_gbs", "_footprint_bytes")] = nbytes
+    flop, ms = tdp.tdp_probe_mfma_bf16(8192, 5, True, stream)
+    out["mfma_bf16_loop_tflops"] = round(flop / ms / 1e9, 1)                       # operands uniform in (-1, 1)
+    flop, ms = tdp.tdp_probe_mfma_bf16(8192, 5, False, stream)
+    out["mfma_bf16_loop_constant_operands_tflops"] = round(flop / ms / 1e9, 1)
+    return out
+
+
 def ends_section(tdp, W, shape, batch, i32, vocab=32000):
     """What the first and the last stage of a pipeline add per decode step: the token-embedding
     lookup, and final RMSNorm + vocabulary projection (fp32 logits) + greedy selection."""
@@ -500,6 +522,15 @@ def main():
         result["prefill"]["curve"] = sorted(curve, key=lambda c: c["tokens"])
         del xp, op
 
+    if not args.layers:
+        emp = empirical_section(tdp, st, shape.n_layers, stream)
+        result["empirical_peaks"] = emp
+        if roof["bound"] == "hbm":
+            roof["frac_of_measured_scattered_read"] = round(roof["achieved"] / emp["hbm_read_4k_scattered_gbs"], 4)
+        if "prefill" in result:
+            result["prefill"]["gemm_frac_of_measured_mfma_loop"] = round(
+                result["prefill"]["gemm_tflops"] / emp["mfma_bf16_loop_tflops"], 4)
+        log("empirical ceilings: %s" % json.dumps(emp))
     st.close()
     torch.cuda.empty_cache()
     if args.kv_fp8 or not (args.layers or args.no_sweep):

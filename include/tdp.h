@@ -225,6 +225,29 @@ TDP_API int tdp_e4m3_from_f32(const float* src, uint8_t* codes, int64_t n, float
 TDP_API int tdp_e4m3_to_f32(const uint8_t* codes, float* dst, int64_t n, void* stream);
 
 /*
+ * Empirical ceilings of the GPU the library runs on, for the benchmark's roofline context (the
+ * decode phase is bound by memory bandwidth and the prefill phase by compute, Sec. 2.1; these say
+ * what the part sustains for either with no other work in the way).  Both calls launch a trivial
+ * kernel `launches` times (1..1000) after one warm-up, time the launches with HIP events on
+ * `stream`, wait for them and return the average milliseconds per launch in *ms_per_launch (host).
+ * tdp_probe_hbm_read: reads the first 2^k * 4 KiB of `buf` (dev, 16-byte aligned, at least 512 KiB;
+ *   2^k * 4 KiB is the largest such size <= bytes, returned in *bytes_per_launch) exactly once per
+ *   launch, 16 bytes per lane per instruction, 16 KiB in flight per wave; scattered = 0 walks the
+ *   4 KiB pieces in address order, 1 in a fixed pseudo-random order (how a paged KV cache is read).
+ *   Nothing is written to `buf`.
+ * tdp_probe_mfma_bf16: `iters` (1..2^22) rounds of sixteen independent 16x16x32 bf16 MFMAs per wave on
+ *   register operands, two waves per SIMD on every CU; *flop_per_launch (host) = multiply-adds * 2.
+ *   random_operands = 1: operands uniform in (-1, 1), different in every lane and element; 0: the
+ *   same constants everywhere (the rate depends on it: the part is power-limited and an MFMA's
+ *   power grows with the operand bits that toggle).
+ * Errors: TDP_EINVAL (null pointer, size or count out of range), TDP_ENOMEM, TDP_EHIP.
+ */
+TDP_API int tdp_probe_hbm_read(const void* buf, int64_t bytes, int32_t scattered, int32_t launches,
+                               int64_t* bytes_per_launch, float* ms_per_launch, void* stream);
+TDP_API int tdp_probe_mfma_bf16(int32_t iters, int32_t launches, int32_t random_operands, double* flop_per_launch,
+                                float* ms_per_launch, void* stream);
+
+/*
  * Timing hooks: when enabled, prefill/decode record HIP events around each kernel class on the
  * call's stream; tdp_stage_timing_read synchronises and returns the summed milliseconds of the
  * most recent call per class (order: rmsnorm, gemm_qkv, rope_kv, attention, gemm_o, gemm_gate_up,

@@ -36,6 +36,11 @@ enum TimeClass { T_NORM = 0, T_QKV, T_ROPE, T_ATTN, T_O, T_GU, T_DOWN, T_COUNT }
 
 }  // namespace
 
+namespace tdp {
+// the error channel for the entry points that live in other files of the library
+int probe_fail(int code, const char* msg) { return fail(code, msg); }
+}  // namespace tdp
+
 struct tdp_stage {
   tdp_stage_config cfg;
   int64_t dq, Nqkv, Nqkv_pad, d_pad, Fpad, Ngu_pad;

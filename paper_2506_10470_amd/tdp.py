@@ -71,6 +71,8 @@ _SIGS = {
     "tdp_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "tdp_e4m3_from_f32": (C.c_int, [_vp, _vp, _i64, C.c_float, _vp]),
     "tdp_e4m3_to_f32": (C.c_int, [_vp, _vp, _i64, _vp]),
+    "tdp_probe_hbm_read": (C.c_int, [_vp, _i64, _i32, _i32, C.POINTER(_i64), C.POINTER(C.c_float), _vp]),
+    "tdp_probe_mfma_bf16": (C.c_int, [_i32, _i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_float), _vp]),
     "tdp_stage_timing_enable": (C.c_int, [_vp, _i32]),
     "tdp_stage_timing_read": (C.c_int, [_vp, C.POINTER(C.c_float)]),
     "tdp_ends_create": (C.c_int, [C.POINTER(EndsConfig), C.POINTER(_vp)]),
@@ -183,6 +185,22 @@ def tdp_e4m3_from_f32(src, codes, n, scale=1.0, stream=None) -> None:
 
 def tdp_e4m3_to_f32(codes, dst, n, stream=None) -> None:
     _check(lib.tdp_e4m3_to_f32(_ptr(codes), _ptr(dst), n, _stream(stream)))
+
+
+def tdp_probe_hbm_read(buf, nbytes: int, scattered: bool, launches: int = 5, stream=None):
+    """-> (bytes read per launch, ms per launch)"""
+    n, ms = _i64(), C.c_float()
+    _check(lib.tdp_probe_hbm_read(_ptr(buf), nbytes, int(bool(scattered)), launches, C.byref(n), C.byref(ms),
+                                  _stream(stream)))
+    return n.value, ms.value
+
+
+def tdp_probe_mfma_bf16(iters: int, launches: int = 5, random_operands: bool = True, stream=None):
+    """-> (flop per launch, ms per launch)"""
+    f, ms = C.c_double(), C.c_float()
+    _check(lib.tdp_probe_mfma_bf16(iters, launches, int(bool(random_operands)), C.byref(f), C.byref(ms),
+                                   _stream(stream)))
+    return f.value, ms.value
 
 
 def tdp_stage_timing_enable(st, on: bool) -> None:

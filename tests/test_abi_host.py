@@ -101,3 +101,23 @@ def test_ends_entry_points_reject_bad_arguments():
     assert tdp.lib.tdp_argmax_rows(None, 1, 8, 8, None, None) == tdp.EINVAL      # null pointers
     assert tdp.lib.tdp_argmax_rows(None, 0, 8, 8, None, None) == tdp.OK          # empty is a no-op
     tdp.lib.tdp_ends_destroy(None)
+
+
+def test_probe_entry_points_reject_bad_arguments():
+    import ctypes as C
+    n, ms, fl = C.c_int64(), C.c_float(), C.c_double()
+    P = tdp.lib.tdp_probe_hbm_read
+    assert P(None, 1 << 20, 0, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # null buffer
+    assert P(4096, 1 << 20, 0, 1, None, C.byref(ms), None) == tdp.EINVAL                # null result
+    assert P(4100, 1 << 20, 0, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # misaligned
+    assert P(4096, 1 << 18, 0, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # below 512 KiB
+    assert P(4096, 1 << 20, 2, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # pattern
+    assert P(4096, 1 << 20, 0, 0, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # launches
+    assert P(4096, 1 << 20, 0, 1001, C.byref(n), C.byref(ms), None) == tdp.EINVAL
+    M = tdp.lib.tdp_probe_mfma_bf16
+    assert M(0, 1, 1, C.byref(fl), C.byref(ms), None) == tdp.EINVAL
+    assert M((1 << 22) + 1, 1, 1, C.byref(fl), C.byref(ms), None) == tdp.EINVAL
+    assert M(16, 0, 1, C.byref(fl), C.byref(ms), None) == tdp.EINVAL
+    assert M(16, 1, 2, C.byref(fl), C.byref(ms), None) == tdp.EINVAL
+    assert M(16, 1, 1, None, C.byref(ms), None) == tdp.EINVAL
+    assert "iters" in tdp.last_error() or "null" in tdp.last_error()

@@ -32,3 +32,15 @@ def test_scheduler_section_on_a_fixed_profile():
     # every policy generates the same tokens; the full policy set is not slower than none of them
     assert pol["td_pipe"]["tok_s"] >= 0.98 * pol["none"]["tok_s"]
     assert out["kv_capacity_tokens"] > 10 ** 6
+
+
+def test_scattered_order_visits_every_piece_once():
+    """The device-side index scrambler is a bijection on [0, 2^bits): same integer arithmetic on the host."""
+    import numpy as np
+    for bits in (7, 8, 13, 18, 22):
+        mask = np.uint64((1 << bits) - 1)
+        g = np.arange(1 << bits, dtype=np.uint64)
+        x = (g * np.uint64(0x9E3779B1)) & np.uint64(0xFFFFFFFF) & mask
+        x ^= x >> np.uint64((bits + 1) // 2)
+        x = (x * np.uint64(0x85EBCA6B)) & np.uint64(0xFFFFFFFF) & mask
+        assert len(np.unique(x)) == 1 << bits, bits
