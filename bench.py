@@ -527,6 +527,12 @@ def main():
         result["empirical_peaks"] = emp
         if roof["bound"] == "hbm":
             roof["frac_of_measured_scattered_read"] = round(roof["achieved"] / emp["hbm_read_4k_scattered_gbs"], 4)
+        # the composite lower bound again, priced at what the probes sustain instead of the published peaks
+        t_min_emp = sum(max(v["alg_bytes_per_launch"] * v["launches_per_step"] / (emp["hbm_read_in_order_gbs"] * 1e9),
+                            v["alg_flops_per_launch"] * v["launches_per_step"] / (emp["mfma_bf16_loop_tflops"] * 1e12))
+                        for v in kern.values()) * 1e3
+        result["decode"]["composite_t_min_at_measured_ceilings_ms"] = round(t_min_emp, 3)
+        result["decode"]["composite_frac_of_measured_ceilings"] = round(t_min_emp / ms, 4)
         if "prefill" in result:
             result["prefill"]["gemm_frac_of_measured_mfma_loop"] = round(
                 result["prefill"]["gemm_tflops"] / emp["mfma_bf16_loop_tflops"], 4)
