@@ -215,6 +215,15 @@ def test_decode_edge_contexts(tdp, shape):
     run_decode_case(tdp, shape, [0, 1, 15, 16, 31, 32, 255, 256, 257, 511, 512, 700])
 
 
+def test_decode_batch_above_512_and_prefill_of_many_short_prompts(tdp):
+    """Sizes on the far side of two internal limits: more than 512 decode rows (no split-K workspace is
+    sized beyond that; the planner's work list takes several requests per thread) and more prompts than
+    a prefill workgroup usually walks past when it looks for its sequence."""
+    rng = np.random.default_rng(520)
+    run_decode_case(tdp, "tiny_gqa", rng.integers(0, 41, size=520))
+    run_prefill_case(tdp, "tiny_gqa", rng.integers(1, 8, size=300), decode_steps=1)
+
+
 def test_decode_is_invariant_under_block_table_permutation(tdp):
     sh = W.SHAPES["tiny_gqa"]
     ctx = np.array([5, 40, 300, 77], dtype=np.int64)
