@@ -178,7 +178,8 @@ __global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __
                                                       const int32_t* __restrict__ cu_seqlens, int n_seqs,
                                                       const int32_t* __restrict__ block_tables,
                                                       int max_pages_per_seq, const float* __restrict__ ws,
-                                                      int splits, int n_tokens, const float* __restrict__ bias) {
+                                                      int splits, int n_tokens, const float* __restrict__ bias,
+                                                      int skip_v) {
   const int t = blockIdx.x;
   // eight consecutive projection outputs of this token, starting at column col
   auto proj8 = [&](const bf16* row, int col, float (&f)[8]) {
@@ -257,6 +258,7 @@ __global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __
       st_bf16x8(dst + half + c0, rb);
     }
   }
+  if (skip_v) return;  // the values are appended page by page (v_append_pages_kernel)
   const int v_col = (n_q_heads + kv.n_kv_heads) * dh;
   for (int w8 = threadIdx.x; w8 < kv.n_kv_heads * dh / 8; w8 += blockDim.x) {
     float f[8];
@@ -276,19 +278,93 @@ __global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __
   }
 }
 
+// Prefill, projection finished in bf16: the values of one page (up to 16 consecutive tokens of one
+// prompt) are appended by one workgroup, so that a channel's row of the transposed V page is written
+// as one piece (token by token every 2-byte store dirtied a 32-byte sector of its own: measured ten
+// times the bytes).  Chunk w of the grid belongs to the last prompt s with cu_seqlens[s] / 16 + s <= w
+// and is page w - (cu_seqlens[s] / 16 + s) of it; the numbering leaves every prompt room for all its
+// pages, chunks past a prompt's last page do nothing.
+__global__ __launch_bounds__(256) void v_append_pages_kernel(const bf16* __restrict__ qkv, int64_t ld, int v_col,
+                                                             KvLayout kv, const int32_t* __restrict__ cu_seqlens,
+                                                             int n_seqs, const int32_t* __restrict__ block_tables,
+                                                             int max_pages_per_seq) {
+  const int w = blockIdx.x;
+  int lo = 0, hi = n_seqs - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if ((cu_seqlens[mid] >> 4) + mid <= w) lo = mid; else hi = mid - 1;
+  }
+  const int t_first = cu_seqlens[lo];
+  const int len = cu_seqlens[lo + 1] - t_first;
+  const int p = w - ((t_first >> 4) + lo);
+  if (p < 0 || p * 16 >= len) return;
+  const int n = min(16, len - p * 16);  // tokens on this page
+  const int64_t page = block_tables[(int64_t)lo * max_pages_per_seq + p];
+  const bf16* src = qkv + (int64_t)(t_first + p * 16) * ld + v_col;
+  const int channels = kv.n_kv_heads * kv.head_dim;
+  for (int c8 = threadIdx.x; c8 < channels / 8; c8 += 256) {
+    bf16x8 in[16];  // [token][8 channels]
+#pragma unroll
+    for (int j = 0; j < 16; ++j) in[j] = j < n ? ld_bf16x8(src + (int64_t)j * ld + c8 * 8) : zero_bf16x8();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      // pools are [page][kv head][channel][16 slots]: channel c8 * 8 + i of all kv heads, counted through
+      const int64_t row = (page * channels + c8 * 8 + i) * 16;
+      if (kv.fp8) {
+        uint8_t* dst = (uint8_t*)kv.v_pool + row;
+        uint4 codes = make_uint4(0u, 0u, 0u, 0u);
+        uint32_t* cw = reinterpret_cast<uint32_t*>(&codes);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cw[j >> 2] |= f32_to_e4m3((float)in[j][i] / kv.v_scale) << (8 * (j & 3));
+        if (n == 16) {
+          *reinterpret_cast<uint4*>(dst) = codes;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 16; ++j)
+            if (j < n) dst[j] = (uint8_t)(cw[j >> 2] >> (8 * (j & 3)));
+        }
+      } else {
+        bf16* dst = (bf16*)kv.v_pool + row;
+        bf16x8 a, b;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          a[j] = in[j][i];
+          b[j] = in[8 + j][i];
+        }
+        if (n == 16) {
+          st_bf16x8(dst, a);
+          st_bf16x8(dst + 8, b);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 16; ++j)
+            if (j < n) dst[j] = in[j][i];
+        }
+      }
+    }
+  }
+}
+
 hipError_t launch_rope_kv(void* qkv, int64_t ld, int n_tokens, int n_q_heads, const KvLayout& kv,
                           const float2* rope_table, int max_pos, const int32_t* ctx_lens,
                           const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
                           int max_pages_per_seq, const float* ws, int splits, const float* bias, hipStream_t s) {
   (void)max_pos;
   if (n_tokens <= 0) return hipSuccess;
-  if (splits > 1)
+  if (splits > 1) {
     rope_kv_kernel<true><<<n_tokens, 1024, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
-                                                  n_seqs, block_tables, max_pages_per_seq, ws, splits, n_tokens, bias);
-  else
+                                                  n_seqs, block_tables, max_pages_per_seq, ws, splits, n_tokens, bias,
+                                                  0);
+  } else {
+    // prefill: the values go page by page; decode (one token per request) has nothing to gather
+    const int paged_v = ctx_lens == nullptr;
     rope_kv_kernel<false><<<n_tokens, 256, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
                                                    n_seqs, block_tables, max_pages_per_seq, nullptr, 1, n_tokens,
-                                                   nullptr);
+                                                   nullptr, paged_v);
+    if (paged_v)
+      v_append_pages_kernel<<<(n_tokens >> 4) + n_seqs + 1, 256, 0, s>>>(
+          (const bf16*)qkv, ld, (n_q_heads + kv.n_kv_heads) * kv.head_dim, kv, cu_seqlens, n_seqs, block_tables,
+          max_pages_per_seq);
+  }
   return hipGetLastError();
 }
 
