@@ -41,8 +41,21 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
   const void* xr = F32_IN ? (const void*)((const float*)x + (int64_t)row * ldx)
                           : (const void*)((const bf16*)x + (int64_t)row * ldx);
   const int chunks = d / 8;
+  // the row is read once: a thread keeps its first KEEP chunks (a row of up to 8192 elements whole) in
+  // registers between the two passes and re-reads only what lies beyond
+  constexpr int KEEP = 4;
+  float keep[KEEP][8];
   float ss = 0.f;
-  for (int c = threadIdx.x; c < chunks; c += 256) {
+#pragma unroll
+  for (int k = 0; k < KEEP; ++k) {
+    const int c = threadIdx.x + 256 * k;
+    if (c < chunks) {
+      load8<F32_IN>(xr, c, keep[k]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss += keep[k][i] * keep[k][i];
+    }
+  }
+  for (int c = threadIdx.x + 256 * KEEP; c < chunks; c += 256) {
     float f[8];
     load8<F32_IN>(xr, c, f);
 #pragma unroll
@@ -54,9 +67,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
   __syncthreads();
   const float tot = red[0] + red[1] + red[2] + red[3];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int c = threadIdx.x; c < chunks; c += 256) {
-    float f[8];
-    load8<F32_IN>(xr, c, f);
+  auto emit = [&](int c, const float (&f)[8]) {
     const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c * 8);
     const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + c * 8 + 4);
     bf16x8 o;
@@ -66,6 +77,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
       o[i + 4] = (bf16)(f[i + 4] * inv * g1[i]);
     }
     st_bf16x8(y + operand_offset(y_lay, row, c * 8), o);
+  };
+#pragma unroll
+  for (int k = 0; k < KEEP; ++k) {
+    const int c = threadIdx.x + 256 * k;
+    if (c < chunks) emit(c, keep[k]);
+  }
+  for (int c = threadIdx.x + 256 * KEEP; c < chunks; c += 256) {
+    float f[8];
+    load8<F32_IN>(xr, c, f);
+    emit(c, f);
   }
 }
 
