@@ -360,7 +360,11 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (BN / 32 / TN) * 64) void gemm_m
   constexpr int BK = 32;
   constexpr int WAVES_N = BN / 32 / TN, WAVES = (BM / (TM * 32)) * WAVES_N;
   constexpr int CPR = BK / 8;         // 16-byte chunks per row
-  constexpr int RW = 256 / (BK * 2);  // rows per 256-byte bank window
+  // Rows that share one swizzle value.  A fragment read of this kernel is 16 rows x 4 chunks (lane =
+  // chunk * 16 + row); measured with SQ_LDS_BANK_CONFLICT on that pattern: the chunk position must
+  // turn every 2 rows to be conflict free (4 LDS cycles per ds_read_b128); turning every 4 rows -
+  // right for the 32 rows x 2 chunks of the 32x32 kernels - costs 8 cycles per read here.
+  constexpr int RW = 2;
   constexpr int RPI = 64 / CPR;       // rows per DMA instruction
   constexpr int IPA = (BM / RPI) / WAVES, IPW = (BN / RPI) / WAVES;
   static_assert(IPA >= 1 && (BM / RPI) % WAVES == 0 && (BN / RPI) % WAVES == 0, "row blocks divide among waves");
