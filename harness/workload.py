@@ -162,6 +162,10 @@ SHAPES: Dict[str, StageShape] = {
                                   rope_base=1000000.0, config_index=5, qkv_bias=True),
     "tiny_bias": StageShape("tiny_bias", 2, 320, 10, 2, 64, 688, rms_eps=1e-6, rope_base=1000000.0,
                             config_index=0, qkv_bias=True),
+    # one K/V head shared by sixteen query heads: the largest group the kernels take
+    "tiny_mqa": StageShape("tiny_mqa", 2, 256, 16, 1, 64, 688, config_index=0),
+    # groups of two query heads (head_dim 128)
+    "tiny_g2": StageShape("tiny_g2", 2, 512, 6, 3, 128, 688, config_index=0),
 }
 
 WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g_attn", "g_mlp")

@@ -204,12 +204,12 @@ def test_prefill_tiny_config(tdp):
     run_prefill_case(tdp, "tiny", W.prefill_seq_lens("tiny", 4))
 
 
-@pytest.mark.parametrize("shape", ["tiny", "tiny_gqa", "tiny_h128", "tiny_bias"])
+@pytest.mark.parametrize("shape", ["tiny", "tiny_gqa", "tiny_h128", "tiny_bias", "tiny_mqa", "tiny_g2"])
 def test_prefill_then_decode_across_page_boundaries(tdp, shape):
     run_prefill_case(tdp, shape, [1, 15, 16, 17, 33, 70], decode_steps=3)
 
 
-@pytest.mark.parametrize("shape", ["tiny_gqa", "tiny_h128", "tiny_bias"])
+@pytest.mark.parametrize("shape", ["tiny_gqa", "tiny_h128", "tiny_bias", "tiny_mqa", "tiny_g2"])
 def test_decode_edge_contexts(tdp, shape):
     """ctx = 0 (attention over the token itself), page edges, split edges (256 tokens per split)."""
     run_decode_case(tdp, shape, [0, 1, 15, 16, 31, 32, 255, 256, 257, 511, 512, 700])
