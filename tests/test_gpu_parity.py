@@ -180,6 +180,9 @@ def run_prefill_case(tdp, shape_name, seq_lens, n_layers=None, stream_id=2, deco
     (513, 520, 448, 9, 2, 1), (70, 260, 128, 11, 1, 0), (65, 512, 256, 12, 2, 1),
     (300, 768, 1024, 13, 1, 0), (257, 516, 192, 13, 2, 1), (100, 384, 256, 14, 3, 0), (130, 1024, 320, 15, 1, 1),
     (100, 384, 256, 16, 2, 0), (300, 640, 1024, 16, 1, 1), (7, 256, 512, 16, 4, 1),
+    # the earlier direct-to-LDS variants stay selectable, so they stay checked
+    (300, 768, 1024, 5, 1, 0), (257, 516, 192, 6, 2, 1), (130, 1024, 320, 7, 1, 1), (100, 384, 256, 8, 3, 0),
+    (300, 640, 1024, 10, 1, 1),
 ])
 def test_gemm_matches_fp64_product(tdp, M, N, K, tile, splits, epi):
     g = torch.Generator(device="cpu").manual_seed(M * 131 + N)
