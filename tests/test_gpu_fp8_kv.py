@@ -250,7 +250,7 @@ def run_decode_case(tdp, shape_name, ctx_lens, scales, n_layers=None, stream_id=
 
 
 @pytest.mark.parametrize("shape,scales", [("tiny", (1.0, 1.0)), ("tiny_gqa", (0.5, 2.0)), ("tiny_h128", (1.0, 1.0)),
-                                          ("tiny_bias", (2.0, 0.25))])
+                                          ("tiny_bias", (2.0, 0.25)), ("tiny_mqa", (1.0, 0.5)), ("tiny_g2", (0.5, 1.0))])
 def test_decode_edge_contexts(tdp, shape, scales):
     """ctx = 0 (attention over the token itself), page edges, block edges (64 tokens), span edges (256)."""
     run_decode_case(tdp, shape, [0, 1, 15, 16, 31, 32, 63, 64, 65, 127, 255, 256, 257, 511, 512, 700], scales)
@@ -297,7 +297,7 @@ def test_dropped_scales_would_be_caught(tdp):
         assert np.max(row_errs(f64(out), np.stack(wrong))) > 3 * TOL
 
 
-@pytest.mark.parametrize("shape", ["tiny_gqa", "tiny_h128"])
+@pytest.mark.parametrize("shape", ["tiny", "tiny_gqa", "tiny_h128", "tiny_mqa", "tiny_g2"])
 def test_prefill_writes_the_cache_and_decode_steps_read_it(tdp, shape):
     """Prefill stores the codes of its keys and values and attends to them; the decode steps that
     follow read the same cache."""
