@@ -227,6 +227,13 @@ def test_decode_batch_above_512_and_prefill_of_many_short_prompts(tdp):
     run_prefill_case(tdp, "tiny_gqa", rng.integers(1, 8, size=300), decode_steps=1)
 
 
+def test_one_request_and_one_token(tdp):
+    """The smallest calls: a decode batch of one request, a prefill of one prompt of one token."""
+    run_decode_case(tdp, "tiny_gqa", [37])
+    run_decode_case(tdp, "tiny_h128", [0])
+    run_prefill_case(tdp, "tiny", [1], decode_steps=2)
+
+
 def test_decode_is_invariant_under_block_table_permutation(tdp):
     sh = W.SHAPES["tiny_gqa"]
     ctx = np.array([5, 40, 300, 77], dtype=np.int64)
