@@ -27,11 +27,14 @@ def dev_view_u8(ptr: int, nbytes: int) -> torch.Tensor:
 class Stage:
     def __init__(self, tdp, shape: W.StageShape, num_pages: int, max_batch: int, max_tokens: int,
                  max_seqs: int, max_pages_per_seq: int, weight_dtype=torch.bfloat16, load_weights=True,
-                 kv_scales=None):
-        """kv_scales: None = bf16 KV pools; (k_scale, v_scale) = 8-bit (E4M3) pools with those scales."""
+                 kv_scales=None, layer_offset: int = 0):
+        """kv_scales: None = bf16 KV pools; (k_scale, v_scale) = 8-bit (E4M3) pools with those scales.
+        layer_offset: the stage's layer l gets the generated weights of model layer layer_offset + l (a
+        later stage of a pipeline)."""
         self.tdp = tdp
         self.shape = shape
         self.kv_scales = kv_scales
+        self.layer_offset = layer_offset
         self.cfg = tdp.StageConfig(
             n_layers=shape.n_layers, d_model=shape.d_model, n_q_heads=shape.n_q_heads,
             n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim, d_ff=shape.d_ff, rms_eps=shape.rms_eps,
@@ -49,7 +52,7 @@ class Stage:
         tdp, sh = self.tdp, self.shape
         for l in range(sh.n_layers):
             for name in W.WEIGHT_NAMES + (W.BIAS_NAMES if sh.qkv_bias else ()):
-                w = W.weight(sh, l, name, device="cuda", dtype=dtype).contiguous()
+                w = W.weight(sh, self.layer_offset + l, name, device="cuda", dtype=dtype).contiguous()
                 rows = w.shape[0]
                 cols = w.shape[1] if w.dim() == 2 else 1
                 tdp.tdp_stage_set_weight(self.h, l, tdp.WEIGHT_IDS[name], w,

@@ -24,14 +24,20 @@ class OutOfPages(RuntimeError):
 
 class StageWorker:
     """Executes prefill / decode / release events on a stage (tdp_stage) and a pair of pipeline ends
-    (tdp_ends) that the caller created and loaded.  `prompts[i]` are request i's prompt token ids."""
+    (tdp_ends) that the caller created and loaded.  `prompts[i]` are request i's prompt token ids.
+    `stage` may also be a sequence of stage handles: the stages of a pipeline held by one GPU, run one
+    after the other on every batch (hidden states handed from each to the next as bf16, the pipeline's
+    hand-over format, Sec. 2.2.3); they share the block tables, every stage owning its own pools of
+    `num_pages` pages."""
 
     def __init__(self, tdp, stage: int, ends: int, d_model: int, num_pages: int, max_pages_per_seq: int,
                  max_batch: int, max_tokens: int, max_seqs: int, prompts: Sequence[Sequence[int]], stream=None,
                  check_tables: bool = False):
         """check_tables: validate every call's block tables on the GPU first (tdp_stage_check_*): one
         synchronisation per call, for runs that test the allocator rather than the throughput."""
-        self.tdp, self.stage, self.ends = tdp, stage, ends
+        self.tdp, self.ends = tdp, ends
+        self.stages = [stage] if isinstance(stage, int) else list(stage)
+        self.stage = self.stages[0]
         self.d_model = d_model
         self.max_pps, self.max_batch, self.max_tokens, self.max_seqs = max_pages_per_seq, max_batch, max_tokens, max_seqs
         self.stream = stream if stream is not None else torch.cuda.current_stream()
@@ -91,7 +97,10 @@ class StageWorker:
         if self.check_tables:
             tdp.tdp_stage_check_prefill(self.stage, cu_dev, table, n, total, self.stream)
         tdp.tdp_embed_tokens(self.ends, self._i32(toks), total, x, self.stream)
-        tdp.tdp_stage_prefill(self.stage, x, cu_dev, table, n, total, y, self.stream)
+        for st in self.stages:
+            tdp.tdp_stage_prefill(st, x, cu_dev, table, n, total, y, self.stream)
+            x, y = y, x
+        y = x
         tdp.tdp_lm_head(self.ends, y, total, self._i32(cu[1:] - 1), n, None, self.next_tok[:n], self.stream)
         for rid, t in zip(ids, self.next_tok[:n].cpu().tolist()):
             self.generated[rid].append(int(t))
@@ -118,7 +127,10 @@ class StageWorker:
         if self.check_tables:
             tdp.tdp_stage_check_decode(self.stage, ctx_dev, table, n, self.stream)
         tdp.tdp_embed_tokens(self.ends, self._i32([self.generated[rid][-1] for rid in ids]), n, x, self.stream)
-        tdp.tdp_stage_decode(self.stage, x, ctx_dev, table, n, y, self.stream)
+        for st in self.stages:
+            tdp.tdp_stage_decode(st, x, ctx_dev, table, n, y, self.stream)
+            x, y = y, x
+        y = x
         tdp.tdp_lm_head(self.ends, y, n, None, n, None, self.next_tok[:n], self.stream)
         for rid, t in zip(ids, self.next_tok[:n].cpu().tolist()):
             self.generated[rid].append(int(t))

@@ -79,6 +79,42 @@ def test_worker_executes_the_oracles_schedule_with_real_kernels(shape, n_stages,
     check_tokens([w.generated[i][0] for i in sample], np.stack(ref_logits))
 
 
+def test_a_pipeline_of_two_stages_on_one_gpu_generates_the_models_tokens():
+    """The worker runs a chain of stages (one layer each here) on every batch, as the stages of a
+    pipeline would on their GPUs: same decisions, same page accounting, and the first tokens are the
+    oracle's for the whole two-layer model."""
+    sh = W.SHAPES["tiny_gqa"]
+    one = sh.with_layers(1)
+    reqs, prompts = make_requests(24, 7)
+    n_stages, capacity, budget = 2, 700, 128
+    max_len = max(r[0] + r[1] for r in reqs) + 1
+    max_pps = (max_len + 15) // 16 + 1
+    num_pages = (capacity + 15) // 16 + len(reqs)
+    rows = max(budget, max_len, len(reqs))
+    with Stage(tdp, one, num_pages, len(reqs), rows, len(reqs), max_pps) as s0, \
+            Stage(tdp, one, num_pages, len(reqs), rows, len(reqs), max_pps, layer_offset=1) as s1, \
+            Ends(sh, VOCAB, rows) as ends:
+        s0.poison()
+        s1.poison()
+        w = StageWorker(tdp, [s0.h, s1.h], ends.h, sh.d_model, num_pages, max_pps, len(reqs), rows, len(reqs), prompts,
+                        check_tables=True)
+        res, ev = w.run(L, L.SimConfig(n_stages, capacity, budget, 1, 1, 1, 1), reqs, DEC, PRE, events_cap=1 << 20)
+        torch.cuda.synchronize()
+    ref = S.simulate(reqs, S.SimConfig(n_stages, capacity, budget, True, True, True, True), DEC, PRE)
+    assert [(k, a, b) for k, _, a, b in ev] == [(k, a, b) for k, _, a, b in ref.events]
+    assert [len(g) for g in w.generated] == [r[1] for r in reqs]
+    assert sorted(w.free_pages) == list(range(num_pages)) and not w.pages
+    layers = list(oracle_layers(sh))          # both layers of the model
+    table, head, gain = f64(w_ends_table(sh)), f64(w_ends_head(sh)), f64(w_ends_gain(sh))
+    sample = [0, 5, 13, 23]
+    ref_logits = []
+    for i in sample:
+        x = E.embed(prompts[i], table)
+        out, _ = O.stage_forward(x, None, layers, oracle_shape(sh))
+        ref_logits.append(E.final_logits(out[-1:], gain, head, sh.rms_eps)[0])
+    check_tokens([w.generated[i][0] for i in sample], np.stack(ref_logits))
+
+
 def w_ends_table(sh):
     return W.ends_weight(sh, "embedding", VOCAB, device="cuda")
 
