@@ -166,6 +166,8 @@ SHAPES: Dict[str, StageShape] = {
     "tiny_mqa": StageShape("tiny_mqa", 2, 256, 16, 1, 64, 688, config_index=0),
     # groups of two query heads (head_dim 128)
     "tiny_g2": StageShape("tiny_g2", 2, 512, 6, 3, 128, 688, config_index=0),
+    # a model dimension beyond 8192 (rows longer than what the row-wise kernels keep in registers)
+    "tiny_wide": StageShape("tiny_wide", 1, 9216, 4, 2, 64, 256, config_index=0),
 }
 
 WEIGHT_NAMES = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g_attn", "g_mlp")

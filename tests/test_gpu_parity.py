@@ -234,6 +234,13 @@ def test_one_request_and_one_token(tdp):
     run_prefill_case(tdp, "tiny", [1], decode_steps=2)
 
 
+def test_model_dimension_above_8192(tdp):
+    """Rows longer than 8192 elements: the row-wise kernels loop where they otherwise hold a row in
+    registers; decode at a batch that splits K (partials summed by the consumers) and a prefill."""
+    run_decode_case(tdp, "tiny_wide", [3, 40, 17, 0, 100, 64, 31, 5])
+    run_prefill_case(tdp, "tiny_wide", [20, 1, 33], decode_steps=1)
+
+
 def test_decode_is_invariant_under_block_table_permutation(tdp):
     sh = W.SHAPES["tiny_gqa"]
     ctx = np.array([5, 40, 300, 77], dtype=np.int64)
