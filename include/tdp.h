@@ -205,11 +205,21 @@ TDP_API int tdp_stage_check_prefill(tdp_stage* st, const int32_t* cu_seqlens, co
 TDP_API int tdp_stage_set_layer_range(tdp_stage* st, int32_t first, int32_t count);
 
 /*
+ * Decode attention splits a request's context into spans of `span_tokens` logical tokens, one
+ * workgroup per (span, K/V head), and merges the spans' partial softmax states in a fixed logical
+ * order (Sec. 2.1: a decode step reads the request's whole cache).  By default the span is chosen
+ * from batch x K/V heads so that small batches still fill the GPU; this call pins it for the
+ * following decode calls (tuning, and tests that walk every span length).  span_tokens: 0 =
+ * automatic, else 256, 512, 1024, 2048 or 4096.  Results agree within rounding whatever the span.
+ */
+TDP_API int tdp_stage_set_decode_span(tdp_stage* st, int32_t span_tokens);
+
+/*
  * Diagnostic: one projection GEMM through the library's kernels, out = A * W with W given as
  * a row-major [K, N] bf16 device matrix (repacked internally on every call: not a fast path).
  * A dev bf16 [M][K]; out dev bf16 [M][N].  K multiple of 64, N multiple of 4.
- * tile: 0 = automatic, 1..16 force a kernel variant; splits: 0 = automatic, else force the split-K
- * factor.  epilogue: 0 = plain store, 1 = out = residual + A*W (residual dev bf16 [M][N]).
+ * tile: 0 = automatic, 1..3 force a kernel variant (256 x 256, 128 x 256, 128 x 128 output tile);
+ * splits: 0 = automatic, else force the split-K factor.  epilogue: 0 = plain store, 1 = out = residual + A*W (residual dev bf16 [M][N]).
  */
 TDP_API int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out, int32_t M, int32_t N,
                   int32_t K, int32_t epilogue, int32_t tile, int32_t splits, void* stream);

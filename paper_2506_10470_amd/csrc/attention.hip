@@ -12,8 +12,6 @@
 // the order that makes a lane's accumulator elements the 8 consecutive tokens it must supply as
 // the "B" operand of O^T[channel][q] += V^T[channel][token] P^T[token][q].
 #include "tdp_device.h"
-#include <stdlib.h>
-
 #include "tdp_kernels.h"
 
 namespace tdp {
@@ -408,10 +406,6 @@ __global__ __launch_bounds__(DH) void attn_decode_merge_kernel(const float* __re
 // Measured on the 70B shape (attention ms per layer at spans 256 / 1024 / 2048 / 4096): batch 16:
 // .032 / .028 / .035 / .046; batch 128: .158 / .138 / .137 / .138; batch 512: .610 / .521 / .494 / .487.
 int attn_decode_span(int batch, int n_kv_heads) {
-  if (const char* e = getenv("TDP_ATTN_SPAN")) {  // tuning aid
-    const int v = atoi(e);
-    if (v == 256 || v == 512 || v == 1024 || v == 2048 || v == 4096) return v;
-  }
   const int units = batch * n_kv_heads;
   return units >= 4096 ? 4096 : units >= 1024 ? 2048 : units >= 128 ? 1024 : kDecodeSpanMin;
 }

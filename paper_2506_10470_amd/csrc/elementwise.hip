@@ -186,41 +186,38 @@ __device__ __forceinline__ void locate_token(int t, const int32_t* ctx_lens, con
 }
 
 // ------------------------------------------------------------------ RoPE + KV append
-// One workgroup per token.  q heads are rotated in place; k heads are rotated and written to the
-// token's slot of the K pool; v heads are written (transposed) to the V pool.  Rotation pairs
-// channel i with channel i + head_dim/2 and turns the pair by pos * base^(-2i/head_dim); the
-// table holds (cos, sin) of that angle, computed in double precision on the host.
-// PARTIALS: the projection arrives as fp32 split-K partials (summed here in split order, plus the
-// bias) instead of a finished bf16 row; the rotation then works on the unrounded sums.
-template <bool PARTIALS>
-__global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __restrict__ qkv, int64_t ld, int n_q_heads,
+// One workgroup per token.  The projection arrives in fp32 - the GEMM's fp32 output, or its split-K
+// partials, summed here in split order (plus the bias) - so the rotation works on unrounded sums and
+// every query and key element is rounded exactly once, after the rotation.  q heads are rotated and
+// written to the bf16 row the attention kernels read; k heads are rotated and written to the token's
+// slot of the K pool; v heads are written (transposed) to the V pool, or, in prefill, rounded into
+// the bf16 row for the page-by-page append that follows.  Rotation pairs channel i with channel
+// i + head_dim/2 and turns the pair by pos * base^(-2i/head_dim); the table holds (cos, sin) of that
+// angle, computed in double precision on the host.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv, int64_t ld, int n_q_heads,
                                                       KvLayout kv, const float2* __restrict__ table,
                                                       const int32_t* __restrict__ ctx_lens,
                                                       const int32_t* __restrict__ cu_seqlens, int n_seqs,
                                                       const int32_t* __restrict__ block_tables,
-                                                      int max_pages_per_seq, const float* __restrict__ ws,
+                                                      int max_pages_per_seq, const float* __restrict__ proj,
                                                       int splits, int n_tokens, const float* __restrict__ bias,
-                                                      int skip_v) {
+                                                      int v_to_row) {
   const int t = blockIdx.x;
   // eight consecutive projection outputs of this token, starting at column col
-  auto proj8 = [&](const bf16* row, int col, float (&f)[8]) {
-    if (PARTIALS) {
+  auto proj8 = [&](int col, float (&f)[8]) {
+    load8<true>(proj + (int64_t)t * ld + col, 0, f);
+    for (int z = 1; z < splits; ++z) {
+      float g[8];
+      load8<true>(proj + ((int64_t)z * n_tokens + t) * ld + col, 0, g);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) f[i] = 0.f;
-      for (int z = 0; z < splits; ++z) {
-        float g[8];
-        load8<true>(ws + ((int64_t)z * n_tokens + t) * ld + col, 0, g);
+      for (int i = 0; i < 8; ++i) f[i] += g[i];
+    }
+    if (bias) {
+      float g[8];
+      load8<true>(bias + col, 0, g);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] += g[i];
-      }
-      if (bias) {
-        float g[8];
-        load8<true>(bias + col, 0, g);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] += g[i];
-      }
-    } else {
-      load8<false>(row + col, 0, f);
+      for (int i = 0; i < 8; ++i) f[i] += g[i];
     }
   };
   int seq, pos;
@@ -234,13 +231,13 @@ __global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __
   const int rot_heads = n_q_heads + kv.n_kv_heads;
   bf16* kpool = (bf16*)kv.k_pool;
   bf16* vpool = (bf16*)kv.v_pool;
-  for (int w = threadIdx.x; w < rot_heads * per_head; w += blockDim.x) {
+  for (int w = threadIdx.x; w < rot_heads * per_head; w += THREADS) {
     const int head = w / per_head;
     const int c0 = (w % per_head) * 8;
     bf16* hp = row + (int64_t)head * dh;
     float a[8], b[8];
-    proj8(row, head * dh + c0, a);
-    proj8(row, head * dh + half + c0, b);
+    proj8(head * dh + c0, a);
+    proj8(head * dh + half + c0, b);
     float fra[8], frb[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -279,11 +276,17 @@ __global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __
       st_bf16x8(dst + half + c0, rb);
     }
   }
-  if (skip_v) return;  // the values are appended page by page (v_append_pages_kernel)
   const int v_col = (n_q_heads + kv.n_kv_heads) * dh;
-  for (int w8 = threadIdx.x; w8 < kv.n_kv_heads * dh / 8; w8 += blockDim.x) {
+  for (int w8 = threadIdx.x; w8 < kv.n_kv_heads * dh / 8; w8 += THREADS) {
     float f[8];
-    proj8(row, v_col + w8 * 8, f);
+    proj8(v_col + w8 * 8, f);
+    if (v_to_row) {  // prefill: the values are appended page by page (v_append_pages_kernel)
+      bf16x8 o;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = (bf16)f[i];
+      st_bf16x8(row + v_col + w8 * 8, o);
+      continue;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int w = w8 * 8 + i;
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(PARTIALS ? 1024 : 256) void rope_kv_kernel(bf16* __
   }
 }
 
-// Prefill, projection finished in bf16: the values of one page (up to 16 consecutive tokens of one
+// Prefill, values rounded to bf16 in the token rows: the values of one page (up to 16 consecutive tokens of one
 // prompt) are appended by one workgroup, so that a channel's row of the transposed V page is written
 // as one piece (token by token every 2-byte store dirtied a 32-byte sector of its own: measured ten
 // times the bytes).  Chunk w of the grid belongs to the last prompt s with cu_seqlens[s] / 16 + s <= w
@@ -368,24 +371,24 @@ __global__ __launch_bounds__(256) void v_append_pages_kernel(const bf16* __restr
 hipError_t launch_rope_kv(void* qkv, int64_t ld, int n_tokens, int n_q_heads, const KvLayout& kv,
                           const float2* rope_table, int max_pos, const int32_t* ctx_lens,
                           const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
-                          int max_pages_per_seq, const float* ws, int splits, const float* bias, hipStream_t s) {
+                          int max_pages_per_seq, const float* proj, int splits, const float* bias, hipStream_t s) {
   (void)max_pos;
   if (n_tokens <= 0) return hipSuccess;
-  if (splits > 1) {
-    rope_kv_kernel<true><<<n_tokens, 1024, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
-                                                  n_seqs, block_tables, max_pages_per_seq, ws, splits, n_tokens, bias,
-                                                  0);
-  } else {
-    // prefill: the values go page by page; decode (one token per request) has nothing to gather
-    const int paged_v = ctx_lens == nullptr;
-    rope_kv_kernel<false><<<n_tokens, 256, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
-                                                   n_seqs, block_tables, max_pages_per_seq, nullptr, 1, n_tokens,
-                                                   nullptr, paged_v);
-    if (paged_v)
-      v_append_pages_kernel<<<(n_tokens >> 4) + n_seqs + 1, 256, 0, s>>>(
-          (const bf16*)qkv, ld, (n_q_heads + kv.n_kv_heads) * kv.head_dim, kv, cu_seqlens, n_seqs, block_tables,
-          max_pages_per_seq);
-  }
+  // prefill: the values go page by page; decode (one token per request) has nothing to gather
+  const int paged_v = ctx_lens == nullptr;
+  // with split-K partials to sum, 1024 threads per row keep all of a thread's loads in flight at once
+  if (splits > 1)
+    rope_kv_kernel<1024><<<n_tokens, 1024, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
+                                                  n_seqs, block_tables, max_pages_per_seq, proj, splits, n_tokens,
+                                                  bias, paged_v);
+  else
+    rope_kv_kernel<256><<<n_tokens, 256, 0, s>>>((bf16*)qkv, ld, n_q_heads, kv, rope_table, ctx_lens, cu_seqlens,
+                                                 n_seqs, block_tables, max_pages_per_seq, proj, 1, n_tokens, bias,
+                                                 paged_v);
+  if (paged_v)
+    v_append_pages_kernel<<<(n_tokens >> 4) + n_seqs + 1, 256, 0, s>>>(
+        (const bf16*)qkv, ld, (n_q_heads + kv.n_kv_heads) * kv.head_dim, kv, cu_seqlens, n_seqs, block_tables,
+        max_pages_per_seq);
   return hipGetLastError();
 }
 

@@ -9,10 +9,11 @@
 // then holds four consecutive output columns n of one row m, which makes the epilogue's stores
 // 8 bytes wide and lets the SwiGLU epilogue find gate and up of one column in the same lane.
 //
-// Tiles are staged through LDS (double buffered, one barrier per 64-wide k-tile) with an XOR
-// swizzle of the 16-byte chunks so that both the staging writes and the fragment reads are free
-// of bank conflicts.  For small M (decode) the K range is split across workgroups and fp32
-// partials are reduced by a second kernel that applies the epilogue.
+// Tiles go from global memory straight into LDS (direct-to-LDS loads, a ring of 32-wide k-stages,
+// one barrier per stage) with an XOR swizzle of the 16-byte chunks applied on the global side, so
+// that the fragment reads are free of bank conflicts.  For small M (decode) the K range is split
+// across workgroups; the fp32 partials are summed by the kernel that consumes the projection, or
+// by a reduce kernel that applies the epilogue.
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -70,58 +71,7 @@ __device__ __forceinline__ void store_row4(const GemmParams& p, int m, int n, fl
   }
 }
 
-// Epilogue shared by the GEMM kernels.  A lane holds, for each (tn, tm, g), output columns
-// n..n+3 of row m, with m = row0 + tm*32 + l32 and n = col0 + tn*32 + g*8 + kg*4.
-template <int TM, int TN>
-__device__ __forceinline__ void gemm_epilogue(const GemmParams& p, f32x16 (&acc)[TN][TM], int row0, int col0,
-                                              int l32, int kg, int split) {
-#pragma unroll
-  for (int tm = 0; tm < TM; ++tm) {
-    const int m = row0 + tm * 32 + l32;
-    if (m >= p.M) continue;
-    if (p.splits > 1) {
-      float* dst = p.ws + ((int64_t)split * p.M + m) * p.Npad;
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = col0 + tn * 32 + g * 8 + kg * 4;
-          f32x4 v = {acc[tn][tm][g * 4 + 0], acc[tn][tm][g * 4 + 1], acc[tn][tm][g * 4 + 2],
-                     acc[tn][tm][g * 4 + 3]};
-          *reinterpret_cast<f32x4*>(dst + n) = v;
-        }
-    } else if (p.epilogue == EPI_SWIGLU) {
-#pragma unroll
-      for (int tn = 0; tn < TN; tn += 2)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int j = (col0 + tn * 32) / 2 + g * 8 + kg * 4;
-          if (j < p.N_store) {
-            bf16x4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              o[e] = (bf16)(silu_f(acc[tn][tm][g * 4 + e]) * acc[tn + 1][tm][g * 4 + e]);
-            *reinterpret_cast<bf16x4*>(p.out + operand_offset(p.u_lay, m, j)) = o;
-          }
-        }
-    } else {
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n = col0 + tn * 32 + g * 8 + kg * 4;
-          if (n < p.N_store) {
-            float v[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = acc[tn][tm][g * 4 + e];
-            store_row4(p, m, n, v);
-          }
-        }
-    }
-  }
-}
-
-// The same epilogue for 16x16 accumulator tiles: a lane holds, for each (wt, at), output columns
+// Epilogue of the GEMM kernel (16x16 accumulator tiles): a lane holds, for each (wt, at), output columns
 // n..n+3 of row m, with m = row0 + at*16 + l16 and n = col0 + wt*16 + kq*4.  Gate and up rows
 // alternate in blocks of 32 weight rows, i.e. tiles wt, wt+1 (gate) pair with wt+2, wt+3 (up).
 template <int AT, int WT>
@@ -177,175 +127,6 @@ __device__ __forceinline__ bool gemm_tile_of_block(const GemmParams& p, int& til
   tile_m = (sb / p.n_sb_n) * p.sb_m + within % p.sb_m;
   tile_n = (sb % p.n_sb_n) * p.sb_n + within / p.sb_m;
   return tile_m < p.tiles_m && tile_n < p.tiles_n;
-}
-
-// BM x 256 output tile fed by direct global->LDS loads (no staging registers).
-//   BM      rows of the activation tile: 256 for prefill and large decode batches, 128 / 64 for
-//           small batches, where the GEMM only streams weights and more, smaller stages are better
-//   BK      k extent of one pipeline stage (64: 128-byte rows, 32: 64-byte rows)
-//   NS      stages resident in LDS; a stage's loads are issued NS-1 barriers before they are used
-//   TM, TN  32x32 MFMA tiles per wave along m / n; waves = (BM/32/TM) x (8/TN)
-//   LOADERS waves that issue the global->LDS loads: all of them, or only the upper half (one per
-//           SIMD), so that while a loader wave is held up at load issue its SIMD-mate, which never
-//           touches the memory pipe, keeps the MFMA unit fed
-// One global_load_lds instruction moves 64 lanes x 16 bytes into 1 KiB of LDS in lane order, so the
-// XOR swizzle is applied on the global side: the lane that fills chunk position c' of row r fetches
-// chunk c' ^ ((r / RW) % CPR) of that row (RW = rows per 256 bytes, CPR = 16-byte chunks per row).
-// With that swizzle the 16 lanes the LDS serves per cycle (16 consecutive rows of one logical
-// chunk) fall into 16 different 16-byte slots of the 64 banks: fragment reads are conflict free.
-template <int BM, int BK, int NS, int TM, int TN, int LOADERS>
-__global__ __launch_bounds__((BM / (TM * 32)) * (8 / TN) * 64) void gemm_dma_kernel(const GemmParams p) {
-  constexpr int BN = 256;
-  constexpr int WAVES_N = 8 / TN, WAVES = (BM / (TM * 32)) * WAVES_N;
-  constexpr int CPR = BK / 8;            // 16-byte chunks per row
-  constexpr int RW = 256 / (BK * 2);     // rows per 256-byte bank window
-  constexpr int RPI = 64 / CPR;          // rows per DMA instruction
-  constexpr int KK = BK / 16;            // MFMA k-steps per stage
-  constexpr int IPA = (BM / RPI) / LOADERS;  // DMA instructions per loader wave per stage: activations
-  constexpr int IPW = (BN / RPI) / LOADERS;  //                                            weights
-  static_assert(LOADERS == WAVES || LOADERS * 2 == WAVES, "all waves load, or the upper half");
-  static_assert(IPA >= 1 && (BM / RPI) % LOADERS == 0 && (BN / RPI) % LOADERS == 0, "row blocks divide among loaders");
-  constexpr int STAGE = (BM + BN) * BK;  // elements per stage: A rows then W rows
-  constexpr int SPT = 64 / BK;           // stages per 64-wide k-tile
-  static_assert(TN % 2 == 0 && KK % 2 == 0, "gate/up pairing and fragment set parity");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);  // [NS][BM + BN][BK]
-
-  int tile_m, tile_n, split;
-  if (!gemm_tile_of_block(p, tile_m, tile_n, split)) return;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm0 = (wave / WAVES_N) * (TM * 32);
-  const int wn0 = (wave % WAVES_N) * (TN * 32);
-  const int l32 = lane & 31;
-  const int kg = lane >> 5;
-  const int m0 = tile_m * BM;
-  const int n0 = tile_n * BN;
-  const int kt_begin = split * p.k_tiles_per_split * SPT;
-  int kt_end = kt_begin + p.k_tiles_per_split * SPT;
-  if (kt_end > p.k_tiles_total * SPT) kt_end = p.k_tiles_total * SPT;
-  const int n_stages = kt_end - kt_begin;
-
-  // DMA assignment: loader wave lw moves row blocks lw*IPA .. (activations) and lw*IPW .. (weights),
-  // RPI rows each.  Addresses are a wave-uniform 64-bit base (tile origin + k) plus a 32-bit
-  // per-lane offset.
-  const bool is_loader = wave >= WAVES - LOADERS;
-  const int lw_id = is_loader ? wave - (WAVES - LOADERS) : 0;
-  const int r_in = lane / CPR;
-  unsigned a_goff[IPA], w_goff[IPW];
-#pragma unroll
-  for (int j = 0; j < IPA; ++j) {
-    const int row = (lw_id * IPA + j) * RPI + r_in;
-    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);  // 16-byte chunk of the stage's k range
-    int m = row;
-    if (m0 + m > p.M - 1) m = p.M - 1 - m0;  // rows past M are clamped: computed, never stored
-    a_goff[j] = (unsigned)(operand_row_offset(p.a_lay, m) + (c_sw >> 2) * p.a_lay.kb + (c_sw & 3) * 8);
-  }
-#pragma unroll
-  for (int j = 0; j < IPW; ++j) {
-    const int row = (lw_id * IPW + j) * RPI + r_in;
-    const int c_sw = (lane % CPR) ^ ((row / RW) % CPR);
-    w_goff[j] = (unsigned)(operand_row_offset(p.w_lay, row) + (c_sw >> 2) * p.w_lay.kb + (c_sw & 3) * 8);
-  }
-  constexpr int KB_PER_STAGE = BK / 32;
-  const bf16* a_base = p.A + operand_row_offset(p.a_lay, m0) + (int64_t)kt_begin * KB_PER_STAGE * p.a_lay.kb;
-  const bf16* w_base = p.W + operand_row_offset(p.w_lay, n0) + (int64_t)kt_begin * KB_PER_STAGE * p.w_lay.kb;
-  // t relative to kt_begin, clamped so the tail re-fetches the last stage (never read)
-  auto dma_stage = [&](int t) {
-    const int tc = t < n_stages ? t : n_stages - 1;
-    const bf16* ab = a_base + (int64_t)tc * KB_PER_STAGE * p.a_lay.kb;
-    const bf16* wb = w_base + (int64_t)tc * KB_PER_STAGE * p.w_lay.kb;
-    bf16* la = smem + (t % NS) * STAGE + lw_id * IPA * RPI * BK;
-    bf16* lw = smem + (t % NS) * STAGE + BM * BK + lw_id * IPW * RPI * BK;
-#pragma unroll
-    for (int j = 0; j < IPA; ++j)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ab + a_goff[j]),
-                                       (__attribute__((address_space(3))) void*)(la + j * RPI * BK), 16, 0, 0);
-#pragma unroll
-    for (int j = 0; j < IPW; ++j)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wb + w_goff[j]),
-                                       (__attribute__((address_space(3))) void*)(lw + j * RPI * BK), 16, 0, 0);
-  };
-
-  f32x16 acc[TN][TM];
-#pragma unroll
-  for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[tn][tm][i] = 0.0f;
-
-  // fragment reads: per-lane row offsets are loop invariant, only the stage base moves
-  int w_off[TN], a_off[TM], w_sw[TN], a_sw[TM];
-#pragma unroll
-  for (int tn = 0; tn < TN; ++tn) {
-    const int r = wn0 + tn * 32 + l32;
-    w_off[tn] = (BM + r) * BK;
-    w_sw[tn] = (r / RW) % CPR;
-  }
-#pragma unroll
-  for (int tm = 0; tm < TM; ++tm) {
-    const int r = wm0 + tm * 32 + l32;
-    a_off[tm] = r * BK;
-    a_sw[tm] = (r / RW) % CPR;
-  }
-  bf16x8 wf[2][TN], af[2][TM];
-  auto read_frags = [&](int t, int kk, int set) {
-    const bf16* base = smem + (t % NS) * STAGE;
-    const int chunk = kk * 2 + kg;
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) wf[set][tn] = ld_bf16x8(base + w_off[tn] + ((chunk ^ w_sw[tn]) << 3));
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) af[set][tm] = ld_bf16x8(base + a_off[tm] + ((chunk ^ a_sw[tm]) << 3));
-  };
-  auto mfma_all = [&](int set) {
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[set][tn], af[set][tm], acc[tn][tm]);
-  };
-  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_DMA = IPA + IPW;  // N_DMA per loader wave per stage
-  // A plain s_barrier is used, not __syncthreads(): its release fence would wait for ALL
-  // outstanding loads and defeat the prefetch distance.  vmcnt(PENDING) = this wave's loads of the
-  // next stage have landed; lgkmcnt(0) = its LDS reads of the buffer refilled next are complete.
-  constexpr int PENDING = (NS - 2) * N_DMA;
-
-  // Pipeline.  The one barrier of stage t sits before its last k-step: by then every wave has
-  // issued (and waited for) its LDS reads of stage t, so right after the barrier buffer t % NS is
-  // refilled with stage t + NS - the loads get a whole stage of MFMA time, barrier to barrier - and
-  // the first fragments of stage t + 1 are read under the last k-step's MFMAs.
-  if (n_stages > 0) {
-    if (is_loader) {
-#pragma unroll
-      for (int t = 0; t < NS - 1; ++t) dma_stage(t);
-    }
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
-    read_frags(0, 0, 0);
-    if (is_loader) dma_stage(NS - 1);
-  }
-  for (int t = 0; t < n_stages; ++t) {
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      if (kk == KK - 1) {
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
-        read_frags(t + 1, 0, 0);
-        if (is_loader) dma_stage(t + NS);
-      } else {
-        read_frags(t, kk + 1, (kk + 1) & 1);
-      }
-      mfma_all(kk & 1);
-#pragma unroll
-      for (int i = 0; i < N_MFMA; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (kk == KK - 1) __builtin_amdgcn_sched_group_barrier(0x010, (N_DMA + N_MFMA - 1) / N_MFMA, 0);
-      }
-    }
-  }
-  // loads still in flight target LDS only; they must land before the workgroup's LDS is released
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  gemm_epilogue<TM, TN>(p, acc, m0 + wm0, n0 + wn0, l32, kg, split);
 }
 
 // The same pipeline on v_mfma_f32_16x16x32_bf16: a stage of 32 k is exactly one MFMA k-step, a wave
@@ -571,163 +352,6 @@ __global__ __launch_bounds__((BM / (TM * 32)) * (BN / 32 / TN) * 64) void gemm_m
   gemm_epilogue16<AT, WT>(p, acc, m0 + wm0, n0 + wn0, l16, kq, split);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(256) void gemm_kernel(const GemmParams p) {
-  constexpr int BK = 64;
-  constexpr int TM = BM / WAVES_M / 32;
-  constexpr int TN = BN / WAVES_N / 32;
-  static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
-  static_assert(TN % 2 == 0, "gate/up pairing needs an even number of 32-row weight tiles per wave");
-  constexpr int A_LOADS = BM / 32;  // 16-byte chunks per thread per k-tile
-  constexpr int W_LOADS = BN / 32;
-
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16* sA = reinterpret_cast<bf16*>(smem_raw);          // [2][BM][64]
-  bf16* sW = sA + 2 * BM * BK;                           // [2][BN][64]
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wm0 = (wave / WAVES_N) * (TM * 32);
-  const int wn0 = (wave % WAVES_N) * (TN * 32);
-  const int l32 = lane & 31;
-  const int kg = lane >> 5;
-
-  int tile_m, tile_n, split;
-  if (!gemm_tile_of_block(p, tile_m, tile_n, split)) return;
-  const int m0 = tile_m * BM;
-  const int n0 = tile_n * BN;
-  const int kt_begin = split * p.k_tiles_per_split;
-  int kt_end = kt_begin + p.k_tiles_per_split;
-  if (kt_end > p.k_tiles_total) kt_end = p.k_tiles_total;
-
-  // staging assignment: thread -> (row = tid/8 + 32 j, chunk = tid%8)
-  const int ld_row = tid >> 3;
-  const int ld_chunk = tid & 7;
-  const bf16* a_ptr[A_LOADS];
-#pragma unroll
-  for (int j = 0; j < A_LOADS; ++j) {
-    int m = m0 + ld_row + 32 * j;
-    if (m > p.M - 1) m = p.M - 1;  // rows past M are clamped: computed, never stored
-    a_ptr[j] = p.A + operand_row_offset(p.a_lay, m) + (ld_chunk >> 2) * p.a_lay.kb + (ld_chunk & 3) * 8;
-  }
-  // weight rows: a wave-uniform base plus a 32-bit offset per row block of 32
-  const bf16* w_ptr = p.W + operand_row_offset(p.w_lay, n0) + (ld_chunk >> 2) * p.w_lay.kb + (ld_chunk & 3) * 8;
-  int w_off[W_LOADS];
-#pragma unroll
-  for (int j = 0; j < W_LOADS; ++j) w_off[j] = (int)operand_row_offset(p.w_lay, ld_row + 32 * j);
-
-  bf16x8 a_reg[A_LOADS], w_reg[W_LOADS];
-  auto load_global = [&](int kt) {
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) a_reg[j] = ld_bf16x8(a_ptr[j] + (int64_t)kt * 2 * p.a_lay.kb);
-#pragma unroll
-    for (int j = 0; j < W_LOADS; ++j) w_reg[j] = ld_bf16x8(w_ptr + w_off[j] + (int64_t)kt * 2 * p.w_lay.kb);
-  };
-  auto store_lds = [&](int buf) {
-    bf16* a = sA + buf * BM * BK;
-    bf16* w = sW + buf * BN * BK;
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
-      const int r = ld_row + 32 * j;
-      st_bf16x8(a + r * BK + ((ld_chunk ^ ((r >> 1) & 7)) << 3), a_reg[j]);
-    }
-#pragma unroll
-    for (int j = 0; j < W_LOADS; ++j) {
-      const int r = ld_row + 32 * j;
-      st_bf16x8(w + r * BK + ((ld_chunk ^ ((r >> 1) & 7)) << 3), w_reg[j]);
-    }
-  };
-
-  f32x16 acc[TN][TM];
-#pragma unroll
-  for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[tn][tm][i] = 0.0f;
-
-  // MFMA fragments, double buffered in registers: the LDS reads of k-step kk+1 are issued
-  // while the MFMAs of k-step kk run.
-  bf16x8 wf[2][TN], af[2][TM];
-  auto read_frags = [&](int buf, int kk, int set) {
-    const bf16* a = sA + buf * BM * BK;
-    const bf16* w = sW + buf * BN * BK;
-    const int chunk = kk * 2 + kg;
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      const int r = wn0 + tn * 32 + l32;
-      wf[set][tn] = ld_bf16x8(w + r * BK + ((chunk ^ ((r >> 1) & 7)) << 3));
-    }
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-      const int r = wm0 + tm * 32 + l32;
-      af[set][tm] = ld_bf16x8(a + r * BK + ((chunk ^ ((r >> 1) & 7)) << 3));
-    }
-  };
-  auto mfma_all = [&](int set) {
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-      for (int tm = 0; tm < TM; ++tm) acc[tn][tm] = mfma32(wf[set][tn], af[set][tm], acc[tn][tm]);
-  };
-  constexpr int N_MFMA = TN * TM, N_FRAG = TN + TM, N_STAGE = A_LOADS + W_LOADS;
-  // Issue-order hints: spread `n_other` instructions of class `mask` evenly between the MFMAs.
-  // (0x008 MFMA, 0x020 VMEM read, 0x100 LDS read, 0x200 LDS write)
-
-  if (kt_begin < kt_end) {
-    load_global(kt_begin);
-    store_lds(0);
-  }
-  __syncthreads();
-  read_frags(0, 0, 0);
-
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    const int buf = (kt - kt_begin) & 1;
-    // branch-free body: the last iteration stages its own tile again (never read)
-    const int kt_next = kt + 1 < kt_end ? kt + 1 : kt;
-    // k-step 0: global loads of the next tile go out, fragments of k-step 1 come in
-    load_global(kt_next);
-    read_frags(buf, 1, 1);
-    mfma_all(0);
-#pragma unroll
-    for (int i = 0; i < N_MFMA; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      if (i < N_STAGE) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-    // k-step 1
-    read_frags(buf, 2, 0);
-    mfma_all(1);
-#pragma unroll
-    for (int i = 0; i < N_MFMA; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    // k-step 2: the staged tile is written to the other LDS buffer
-    read_frags(buf, 3, 1);
-    store_lds(buf ^ 1);
-    mfma_all(0);
-#pragma unroll
-    for (int i = 0; i < N_MFMA; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      if (i < N_STAGE) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-    }
-    __syncthreads();
-    // k-step 3: fragments of the next tile's k-step 0 come in from the other buffer
-    read_frags(buf ^ 1, 0, 0);
-    mfma_all(1);
-#pragma unroll
-    for (int i = 0; i < N_MFMA; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < N_FRAG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-  }
-
-  gemm_epilogue<TM, TN>(p, acc, m0 + wm0, n0 + wn0, l32, kg, split);
-}
-
 // Sum the split-K partials and apply the epilogue.  One thread per 4 output columns.
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, int out_cols) {
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -758,89 +382,44 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const GemmParams p, in
 struct TileInfo {
   int bm, bn, lds_bytes, wg_per_cu;
 };
-static const TileInfo kTiles[17] = {
+// kernel variants, selectable through GemmArgs::force_tile (1 .. kGemmTileMax)
+static const TileInfo kTiles[kGemmTileMax + 1] = {
     {0, 0, 0, 0},
-    {256, 256, 2 * (256 + 256) * 128, 1},
-    {128, 128, 2 * (128 + 128) * 128, 2},
-    {64, 128, 2 * (64 + 128) * 128, 3},
-    {32, 256, 2 * (32 + 256) * 128, 2},
-    {256, 256, 4 * 512 * 64, 1},   // 5: direct-to-LDS, BK 32 x 4 stages, 8 waves
-    {256, 256, 2 * 512 * 128, 1},  // 6: direct-to-LDS, BK 64 x 2 stages, 8 waves, 4 of them load
-    {256, 256, 2 * 512 * 128, 1},  // 7: direct-to-LDS, BK 64 x 2 stages, 4 waves
-    {256, 256, 2 * 512 * 128, 1},  // 8: direct-to-LDS, BK 64 x 2 stages, 8 waves, every wave loads
-    {256, 256, 4 * 512 * 64, 1},   // 9: direct-to-LDS, BK 32 x 4 stages, 4 waves
-    {256, 256, 5 * 512 * 64, 1},   // 10: direct-to-LDS, BK 32 x 5 stages (all 160 KiB of LDS), 4 waves
-    {128, 256, 6 * 384 * 64, 1},   // 11: direct-to-LDS, 128 x 256 tile, BK 32 x 6 stages, 4 waves
-    {64, 256, 4 * 320 * 64, 2},    // 12: direct-to-LDS, 64 x 256 tile, BK 32 x 4 stages, 4 waves
-    {256, 256, 4 * 512 * 64, 1},   // 13: as 9 on 16x16x32 MFMA tiles
-    {128, 256, 6 * 384 * 64, 1},   // 14: as 11 on 16x16x32 MFMA tiles
-    {256, 256, 5 * 512 * 64, 1},   // 15: as 10 on 16x16x32 MFMA tiles
-    {128, 128, 4 * 256 * 64, 2},   // 16: 128 x 128 tile on 16x16x32 MFMA tiles, BK 32 x 4 stages, two workgroups per CU
+    {256, 256, 4 * 512 * 64, 1},   // 1: 256 x 256 tile, BK 32 x 4 stages, four waves of 128 x 128
+    {128, 256, 6 * 384 * 64, 1},   // 2: 128 x 256 tile, BK 32 x 6 stages, four waves of 64 x 128
+    {128, 128, 4 * 256 * 64, 2},   // 3: 128 x 128 tile, BK 32 x 4 stages, four waves of 64 x 64, two workgroups per CU
 };
 
+static bool g_print_plan = false;  // tuning aid, read from the environment once (gemm_setup)
+
 hipError_t gemm_setup() {
-  hipError_t e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<256, 256, 2, 2>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[1].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<128, 128, 2, 2>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[2].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<64, 128, 2, 2>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[3].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_kernel<32, 256, 1, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[4].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 32, 4, 4, 2, 8>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[5].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 64, 2, 4, 2, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[6].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 64, 2, 4, 4, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[7].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 64, 2, 4, 2, 8>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[8].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 32, 4, 4, 4, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[9].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<256, 32, 5, 4, 4, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[10].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<128, 32, 6, 2, 4, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[11].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<64, 32, 4, 2, 2, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[12].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<256, 4, 4, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[13].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<128, 6, 2, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[14].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<256, 5, 4, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[15].lds_bytes);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<128, 4, 2, 2, 128>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[16].lds_bytes);
-  return e;
+  static std::once_flag once;
+  static hipError_t result = hipSuccess;
+  std::call_once(once, [] {
+    g_print_plan = getenv("TDP_GEMM_PLAN") != nullptr;
+    hipError_t e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<256, 4, 4, 4>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[1].lds_bytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<128, 6, 2, 4>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[2].lds_bytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_mi16_kernel<128, 4, 2, 2, 128>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kTiles[3].lds_bytes);
+    result = e;
+  });
+  return result;
 }
 
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0) return hipSuccess;
   int t = a.force_tile;
-  if (t < 1 || t > 16) {
+  if (t < 1 || t > kGemmTileMax) {
     // up to 256 rows a projection with few weight rows and a short K fills the chip better with
     // 128-row tiles (twice the workgroups, half the split-K factor); measured at M = 256, K = 8192:
     // 59 vs 72 us (N 10240), 50 vs 61 (N 8192); with K = 28672 the 256-row tile stays ahead (141 vs 148)
     const bool narrow = a.Npad <= 16384 && a.Kpad <= 16384;
-    // (down to a single row the direct-to-LDS kernel streams the weights as fast as or faster than the
-    // register-staged 32-row one, tile 4: 5.8 vs 5.7 TB/s on gate/up, 4.1-4.6 vs 4.0-4.5 on the small projections)
-    t = a.M <= 128 ? 14 : (a.M <= 256 && narrow) ? 14 : 13;
+    t = a.M <= 128 ? 2 : (a.M <= 256 && narrow) ? 2 : 1;
   }
   const TileInfo& ti = kTiles[t];
   GemmParams p;
@@ -957,28 +536,14 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.sb_n = best_sb / p.sb_m;
   p.n_sb_n = (p.tiles_n + p.sb_n - 1) / p.sb_n;
   p.n_sb = ((p.tiles_m + p.sb_m - 1) / p.sb_m) * p.n_sb_n;
-  static const bool print_plan = getenv("TDP_GEMM_PLAN") != nullptr;
-  if (print_plan)
+  if (g_print_plan)
     fprintf(stderr, "gemm plan: M=%d N=%lld K=%lld tile=%d tiles=%dx%d splits=%d (k-tiles %d each) super-block %dx%d\n",
             a.M, (long long)a.Npad, (long long)a.Kpad, t, p.tiles_m, p.tiles_n, splits, p.k_tiles_per_split, p.sb_m,
             p.sb_n);
-  dim3 grid(((p.n_sb * splits + 7) / 8) * 8 * p.sb_m * p.sb_n), block(256);
+  dim3 grid(((p.n_sb * splits + 7) / 8) * 8 * p.sb_m * p.sb_n);
   switch (t) {
-    case 1: gemm_kernel<256, 256, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
-    case 2: gemm_kernel<128, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
-    case 3: gemm_kernel<64, 128, 2, 2><<<grid, block, ti.lds_bytes, s>>>(p); break;
-    case 4: gemm_kernel<32, 256, 1, 4><<<grid, block, ti.lds_bytes, s>>>(p); break;
-    case 5: gemm_dma_kernel<256, 32, 4, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 6: gemm_dma_kernel<256, 64, 2, 4, 2, 4><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 7: gemm_dma_kernel<256, 64, 2, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 8: gemm_dma_kernel<256, 64, 2, 4, 2, 8><<<grid, dim3(512), ti.lds_bytes, s>>>(p); break;
-    case 9: gemm_dma_kernel<256, 32, 4, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 10: gemm_dma_kernel<256, 32, 5, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 11: gemm_dma_kernel<128, 32, 6, 2, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 12: gemm_dma_kernel<64, 32, 4, 2, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 13: gemm_mi16_kernel<256, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 14: gemm_mi16_kernel<128, 6, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
-    case 15: gemm_mi16_kernel<256, 5, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 1: gemm_mi16_kernel<256, 4, 4, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
+    case 2: gemm_mi16_kernel<128, 6, 2, 4><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
     default: gemm_mi16_kernel<128, 4, 2, 2, 128><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
   }
   hipError_t e = hipGetLastError();

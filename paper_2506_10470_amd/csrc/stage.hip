@@ -53,6 +53,7 @@ struct tdp_stage {
   int64_t pool_bytes = 0;  // pool_elems * (2: bf16 | 1: E4M3 codes)
   float k_scale = 1.f, v_scale = 1.f;
   uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *u = nullptr;  // bf16 activations
+  float* qkv32 = nullptr;  // the QKV projection as the GEMM leaves it (fp32): rotated before its one rounding
   float *h = nullptr, *xa = nullptr, *xb = nullptr;  // residual stream, fp32 between layers
   float* ws = nullptr;
   int64_t ws_elems = 0;
@@ -66,6 +67,7 @@ struct tdp_stage {
   int max_pos = 0;
   int maxM = 0;
   int layer_first = 0, layer_count = 0;  // count 0 = all layers
+  int decode_span = 0;                   // 0 = chosen from the batch size
   bool timing = false;
   std::vector<hipEvent_t> ev_start, ev_stop;
   std::vector<int> ev_class;
@@ -161,7 +163,7 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
   // 20-layer stage to more than the 2e-2 parity bound.
   const void* x = hidden_in;
   int x_f32 = 0;
-  const int span_len = attn_decode_span(M, c.n_kv_heads);
+  const int span_len = st->decode_span > 0 ? st->decode_span : attn_decode_span(M, c.n_kv_heads);
   if (ctx_lens)
     HIP_TRY(launch_attn_plan(ctx_lens, block_tables, c.max_pages_per_seq, M, st->max_chunks, span_len, st->attn_items,
                              st->attn_n_items, st->attn_item_pages, s));
@@ -195,17 +197,20 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
       Timer t(st, s, T_QKV);
       g.A = st->y; g.a_layout = layout_paired(d);
       g.W = st->wqkv + (int64_t)l * st->Nqkv_pad * d; g.Kpad = d; g.Npad = st->Nqkv_pad;
-      g.N_store = (int)st->Nqkv_pad; g.out = st->qkv; g.ldo = st->Nqkv_pad;
-      g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE; g.out_f32 = 0; g.residual_f32 = 0;
+      g.N_store = (int)st->Nqkv_pad; g.out = st->qkv32; g.ldo = st->Nqkv_pad;
+      g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE; g.out_f32 = 1; g.residual_f32 = 0;
       g.bias = st->has_bias ? st->bqkv + (int64_t)l * st->Nqkv_pad : nullptr;
       g.splits_used = fuse_reduce ? &qkv_splits : nullptr;
       HIP_TRY(launch_gemm(g, s));
       g.splits_used = nullptr;
     }
-    {  // a3: rotary embedding + KV append (sums the projection's partials and adds the bias if it was split)
+    {  // a3: rotary embedding + KV append, from the fp32 projection (if it was split: sums the partials and
+       // adds the bias, which the GEMM's epilogue has done otherwise)
       Timer t(st, s, T_ROPE);
+      const bool split = qkv_splits > 1;
       HIP_TRY(launch_rope_kv(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, st->rope_table, st->max_pos, ctx_lens,
-                             cu_seqlens, n_seqs, block_tables, c.max_pages_per_seq, st->ws, qkv_splits, g.bias, s));
+                             cu_seqlens, n_seqs, block_tables, c.max_pages_per_seq, split ? st->ws : st->qkv32,
+                             qkv_splits, split ? g.bias : nullptr, s));
       g.bias = nullptr;
     }
     {  // a4: attention
@@ -265,7 +270,7 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
 
 extern "C" {
 
-int tdp_abi_version(void) { return 2; }
+int tdp_abi_version(void) { return 3; }
 
 const char* tdp_last_error(void) { return g_err.c_str(); }
 
@@ -310,6 +315,7 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
   const int64_t M = (st->maxM + 1) & ~1;  // row pairs: pair-interleaved activation buffers
   A(&st->y, M * d, true);
   A(&st->qkv, M * st->Nqkv_pad, true);
+  A(&st->qkv32, M * st->Nqkv_pad, true);
   A(&st->attn, M * st->dq, true);
   A(&st->h, M * d, true);
   A(&st->u, M * st->Fpad, true);
@@ -358,7 +364,7 @@ void tdp_stage_destroy(tdp_stage* st) {
   if (!st) return;
   (void)hipDeviceSynchronize();
   void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->bqkv, st->kpool, st->vpool, st->y,
-                  st->qkv, st->attn, st->h, st->u, st->xa, st->xb, st->ws, st->part_o, st->part_ml,
+                  st->qkv, st->qkv32, st->attn, st->h, st->u, st->xa, st->xb, st->ws, st->part_o, st->part_ml,
                   st->attn_items, st->attn_n_items, st->attn_item_pages, st->rope_table, st->check_owner,
                   st->check_res};
   for (void* p : ptrs)
@@ -547,7 +553,7 @@ int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out,
   if (M < 0 || N <= 0 || K <= 0) return fail(TDP_EINVAL, "bad GEMM shape");
   if (K % 64 || N % 4) return fail(TDP_EINVAL, "K must be a multiple of 64 and N of 4");
   if (epilogue != 0 && epilogue != 1) return fail(TDP_EINVAL, "epilogue must be 0 or 1");
-  if (tile < 0 || tile > 16 || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
+  if (tile < 0 || tile > kGemmTileMax || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
   if (M == 0) return TDP_OK;
   if (!A || !W || !out || (epilogue == 1 && !residual)) return fail(TDP_EINVAL, "null pointer");
   hipStream_t s = (hipStream_t)stream;
@@ -604,6 +610,15 @@ int tdp_stage_set_layer_range(tdp_stage* st, int32_t first, int32_t count) {
     return fail(TDP_EINVAL, "layer range outside the stage");
   st->layer_first = first;
   st->layer_count = count;
+  return TDP_OK;
+}
+
+int tdp_stage_set_decode_span(tdp_stage* st, int32_t span_tokens) {
+  if (!st) return fail(TDP_EINVAL, "null stage");
+  if (span_tokens != 0 && span_tokens != 256 && span_tokens != 512 && span_tokens != 1024 && span_tokens != 2048 &&
+      span_tokens != 4096)
+    return fail(TDP_EINVAL, "span must be 0 (automatic), 256, 512, 1024, 2048 or 4096 tokens");
+  st->decode_span = span_tokens;
   return TDP_OK;
 }
 

@@ -38,6 +38,7 @@ enum Epilogue : int {
                      //                                   in blocks of 32: gate block, up block)
 };
 
+constexpr int kGemmTileMax = 3;  // kernel variants: 1 = 256 x 256 tile, 2 = 128 x 256, 3 = 128 x 128
 struct GemmArgs {
   const void* A;      // bf16, M rows x Kpad columns in a_layout; rows >= M are never read
   OperandLayout a_layout;
@@ -57,7 +58,7 @@ struct GemmArgs {
   int residual_f32;
   float* workspace;       // fp32 split-K partials
   int64_t workspace_elems;
-  int force_tile;         // 0 = choose; else 1..4 selects a tile shape (tests / tuning)
+  int force_tile;         // 0 = choose; else 1..kGemmTileMax selects a kernel variant (tests / tuning)
   int force_splits;       // 0 = choose
   // Deferred reduction (plain and residual epilogues only): when the plan splits K, leave the fp32
   // partials in the workspace, ws[(z * M + m) * Npad + n] for split z, apply nothing and launch no
@@ -103,12 +104,13 @@ struct KvLayout {
 };
 // decode: token b sits at position ctx_lens[b] of sequence b.  prefill: token t of sequence s
 // (cu_seqlens[s] <= t < cu_seqlens[s+1]) sits at position t - cu_seqlens[s].
-// With splits > 1 the projection is read as fp32 split-K partials, ws[(z * n_tokens + t) * ld + :] (+ bias if
-// given), instead of the bf16 row qkv[t]; the rotated queries are written to qkv either way.
+// The projection is read in fp32: proj[(z * n_tokens + t) * ld + :] summed over the `splits` split-K
+// partials z (splits = 1: the GEMM's finished fp32 output), plus `bias` if given.  The rotated
+// queries are written to the bf16 rows qkv[t] (same ld), and so are the values in prefill.
 hipError_t launch_rope_kv(void* qkv, int64_t ld, int n_tokens, int n_q_heads, const KvLayout& kv,
                           const float2* rope_table, int max_pos, const int32_t* ctx_lens,
                           const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
-                          int max_pages_per_seq, const float* ws, int splits, const float* bias, hipStream_t s);
+                          int max_pages_per_seq, const float* proj, int splits, const float* bias, hipStream_t s);
 // KV import/export between packed logical order [tokens][Hkv][dh] and the paged pools.
 hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const KvLayout& kv,
                           const int32_t* cu_seqlens, int n_seqs, int total_tokens,

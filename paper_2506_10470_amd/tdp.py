@@ -68,6 +68,7 @@ _SIGS = {
     "tdp_stage_check_decode": (C.c_int, [_vp, _vp, _vp, _i32, _vp]),
     "tdp_stage_check_prefill": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "tdp_stage_set_layer_range": (C.c_int, [_vp, _i32, _i32]),
+    "tdp_stage_set_decode_span": (C.c_int, [_vp, _i32]),
     "tdp_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "tdp_e4m3_from_f32": (C.c_int, [_vp, _vp, _i64, C.c_float, _vp]),
     "tdp_e4m3_to_f32": (C.c_int, [_vp, _vp, _i64, _vp]),
@@ -172,6 +173,10 @@ def tdp_stage_check_prefill(st, cu_seqlens, block_tables, n_seqs, total_tokens, 
 
 def tdp_stage_set_layer_range(st, first: int, count: int) -> None:
     _check(lib.tdp_stage_set_layer_range(st, first, count))
+
+
+def tdp_stage_set_decode_span(st, span_tokens: int) -> None:
+    _check(lib.tdp_stage_set_decode_span(st, span_tokens))
 
 
 def tdp_gemm_bf16(A, W, residual, out, M, N, K, epilogue=0, tile=0, splits=0, stream=None) -> None:

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     for name in declared:
         assert hasattr(tdp.lib, name), name
         assert name in tdp._SIGS, "binding lacks " + name
-    assert tdp.tdp_abi_version() == 2
+    assert tdp.tdp_abi_version() == 3
 
 
 @pytest.mark.parametrize("bad", [
@@ -78,6 +78,7 @@ def test_gemm_entry_rejects_bad_shapes():
 def test_layer_range_and_timing_calls_reject_null_stage():
     assert tdp.lib.tdp_stage_set_layer_range(None, 0, 1) == tdp.EINVAL
     assert tdp.lib.tdp_stage_timing_enable(None, 1) == tdp.EINVAL
+    assert tdp.lib.tdp_stage_set_decode_span(None, 256) == tdp.EINVAL
     assert tdp.lib.tdp_stage_kv_import(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL
     assert tdp.lib.tdp_stage_kv_export(None, 0, None, None, None, None, 1, 1, None) == tdp.EINVAL
     assert tdp.lib.tdp_stage_check_decode(None, None, None, 1, None) == tdp.EINVAL

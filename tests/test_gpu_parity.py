@@ -82,7 +82,7 @@ def written_slot_mask(st: Stage, tables: np.ndarray, first: np.ndarray, last: np
     return mk, mv
 
 
-def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_pages_per_seq=None):
+def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_pages_per_seq=None, span=0):
     sh = W.SHAPES[shape_name]
     if n_layers:
         sh = sh.with_layers(n_layers)
@@ -91,6 +91,7 @@ def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_p
     batch = W.make_decode_batch(ctx_lens, max_pages_per_seq=max_pages_per_seq)
     with Stage(tdp, sh, batch.num_pages, B, 0, 0, batch.tables.shape[1]) as st:
         st.poison()
+        tdp.tdp_stage_set_decode_span(st.h, span)
         caches = import_kv(tdp, st, ctx_lens, batch.tables, stream_id)
         before = [tuple(t.clone() for t in st.pools(l)) for l in range(sh.n_layers)]
         x = W.hidden_states(sh, B, stream_id, device="cuda")
@@ -173,16 +174,13 @@ def run_prefill_case(tdp, shape_name, seq_lens, n_layers=None, stream_id=2, deco
 # ----------------------------------------------------------------------------- GEMM alone
 
 @pytest.mark.parametrize("M,N,K,tile,splits,epi", [
-    (4, 768, 256, 0, 0, 0), (4, 256, 704, 0, 0, 1), (33, 320, 128, 4, 2, 0), (64, 512, 512, 3, 1, 1),
-    (100, 384, 256, 2, 3, 0), (130, 1024, 320, 2, 1, 1), (300, 768, 1024, 1, 1, 0), (257, 516, 192, 1, 2, 1),
-    (512, 1280, 2048, 0, 0, 0), (1000, 256, 64, 0, 0, 1),
-    # the direct-to-LDS variants: 32x32x16 tiles (9, 11, 12) and 16x16x32 tiles (13, 14, 15, 16), ragged M, split-K
-    (513, 520, 448, 9, 2, 1), (70, 260, 128, 11, 1, 0), (65, 512, 256, 12, 2, 1),
-    (300, 768, 1024, 13, 1, 0), (257, 516, 192, 13, 2, 1), (100, 384, 256, 14, 3, 0), (130, 1024, 320, 15, 1, 1),
-    (100, 384, 256, 16, 2, 0), (300, 640, 1024, 16, 1, 1), (7, 256, 512, 16, 4, 1),
-    # the earlier direct-to-LDS variants stay selectable, so they stay checked
-    (300, 768, 1024, 5, 1, 0), (257, 516, 192, 6, 2, 1), (130, 1024, 320, 7, 1, 1), (100, 384, 256, 8, 3, 0),
-    (300, 640, 1024, 10, 1, 1),
+    # the planner's own choice
+    (4, 768, 256, 0, 0, 0), (4, 256, 704, 0, 0, 1), (33, 320, 128, 0, 2, 0), (64, 512, 512, 0, 1, 1),
+    (512, 1280, 2048, 0, 0, 0), (1000, 256, 64, 0, 0, 1), (257, 516, 192, 0, 2, 1),
+    # every kernel variant (1: 256 x 256 tile, 2: 128 x 256, 3: 128 x 128), ragged M and N, split-K
+    (300, 768, 1024, 1, 1, 0), (257, 516, 192, 1, 2, 1), (513, 520, 448, 1, 2, 1),
+    (100, 384, 256, 2, 3, 0), (130, 1024, 320, 2, 1, 1), (70, 260, 128, 2, 1, 0), (65, 512, 256, 2, 2, 1),
+    (100, 384, 256, 3, 2, 0), (300, 640, 1024, 3, 1, 1), (7, 256, 512, 3, 4, 1),
 ])
 def test_gemm_matches_fp64_product(tdp, M, N, K, tile, splits, epi):
     g = torch.Generator(device="cpu").manual_seed(M * 131 + N)
@@ -361,6 +359,40 @@ def test_prefill_7b_shaped_layer_many_tiles(tdp):
     run_prefill_case(tdp, "7b_quarter", [200, 31, 129, 64, 103], n_layers=1)
 
 
+@pytest.mark.parametrize("shape,seq_lens", [
+    # one head per workgroup (multi-head attention and groups that no power of two divides): a query
+    # tile is 256 positions
+    ("tiny", [4096]),                       # head_dim 64, sixteen query tiles, 257 pages
+    ("tiny", [257, 300, 513, 1000, 256]),   # tile edges: one position into a second tile, exact multiples
+    ("tiny_bias", [700, 259]),              # group of 5 -> one head per workgroup
+    # two heads per workgroup: 128 positions per tile
+    ("tiny_g2", [300, 129, 257, 128]),
+    # four and eight heads per workgroup: 64 and 32 positions per tile
+    ("tiny_gqa", [200, 65, 64, 449]),
+    ("tiny_h128", [130, 577]),
+    ("tiny_mqa", [100, 33, 32, 290]),
+])
+def test_prefill_attention_beyond_one_query_tile(tdp, shape, seq_lens):
+    """Prompts longer than one query tile of every prefill-attention variant (Sec. 2.1: the prefill
+    phase processes all tokens of a prompt at once): later tiles start at a position above zero, skip
+    the key blocks beyond their diagonal and stop at their own end of the prompt.  Outputs, the cached
+    keys and values and the untouched slots are compared as in the short cases; one decode step
+    follows on the cache the prefill wrote."""
+    run_prefill_case(tdp, shape, seq_lens, decode_steps=1)
+
+
+def test_prefill_7b_shaped_layer_prompts_of_several_query_tiles(tdp):
+    """One 7B-shaped layer (32 heads x 128, multi-head attention: 256 query positions per workgroup)
+    on prompts of 257 to 1000 tokens."""
+    run_prefill_case(tdp, "7b_quarter", [257, 300, 513, 1000], n_layers=1)
+
+
+def test_prefill_13b_shaped_layer_longest_prompt_of_its_benchmark_batch(tdp):
+    """One 13B-shaped layer (40 heads x 128) on a prompt as long as the longest of the 32-prompt
+    benchmark batch (1838 tokens: eight query tiles per head)."""
+    run_prefill_case(tdp, "13b_quarter", [int(W.prefill_seq_lens("13b_quarter", 32).max())], n_layers=1)
+
+
 def test_decode_70b_shaped_layer_gqa(tdp):
     """One 70B-shaped layer (64 query heads on 8 KV heads), batch 24."""
     ctx = np.minimum(W.decode_ctx_lens("70b_quarter", 24), 700)
@@ -407,14 +439,16 @@ def test_a_dropped_bias_would_be_caught(tdp):
 
 
 @pytest.mark.parametrize("span", [256, 512, 1024, 2048, 4096])
-def test_decode_every_span_length(tdp, span, monkeypatch):
+def test_decode_every_span_length(tdp, span):
     """The library picks the span length (tokens of one context handled by one workgroup) from the
-    batch size; TDP_ATTN_SPAN forces it.  Contexts sit on and around the span boundaries, so
+    batch size; tdp_stage_set_decode_span pins it.  Contexts sit on and around the span boundaries, so
     requests finish inside one workgroup, need exactly two partials, or end one token into a span."""
-    monkeypatch.setenv("TDP_ATTN_SPAN", str(span))
     ctx = sorted({0, 31, span - 2, span - 1, span, span + 1, 2 * span - 1, 2 * span, 2 * span + 33,
                   min(3 * span + 7, 4096)} & set(range(0, 4097)))
-    run_decode_case(tdp, "tiny_gqa", ctx, n_layers=1, max_pages_per_seq=4096 // 16 + 1)
+    run_decode_case(tdp, "tiny_gqa", ctx, n_layers=1, max_pages_per_seq=4096 // 16 + 1, span=span)
+    with Stage(tdp, W.SHAPES["tiny"], 4, 1, 0, 0, 2, load_weights=False) as st:
+        with pytest.raises(tdp.TdpError):
+            tdp.tdp_stage_set_decode_span(st.h, 300)
 
 
 def test_decode_step_replays_from_a_hip_graph(tdp):
