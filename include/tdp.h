@@ -225,6 +225,21 @@ TDP_API int tdp_gemm_bf16(const void* A, const void* W, const void* residual, vo
                   int32_t K, int32_t epilogue, int32_t tile, int32_t splits, void* stream);
 
 /*
+ * tdp_gemm_bf16 for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results, but
+ * the repacked weights and the split-K partials live in a device array that is part of the library
+ * image (64 MiB per GPU, held until the process ends) instead of two allocations per call.  The
+ * call allocates and frees nothing and only enqueues on `stream` (it does not wait; the caller
+ * synchronises before reading `out`).  Limits: N rounded up to a multiple of 256, times K, at most
+ * 8 Mi elements (16 MiB of weights); (splits, or 16 when splits = 0) * M * that N at most 12 Mi
+ * floats (48 MiB of partials); anything larger is TDP_EINVAL with a message naming the limit, checked
+ * before any GPU work.  All calls on one GPU share the one array: calls that may overlap (different
+ * streams without an order between them, or several threads) race; calls on one stream are safe.
+ */
+TDP_API int tdp_gemm_bf16_static(const void* A, const void* W, const void* residual, void* out, int32_t M,
+                                 int32_t N, int32_t K, int32_t epilogue, int32_t tile, int32_t splits, void* stream);
+
+/*
  * Diagnostics for the 8-bit cache format: the conversions exactly as the KV kernels perform them.
  * tdp_e4m3_from_f32: codes[i] = E4M3 code of src[i] / scale (dev fp32 -> dev bytes; scale > 0).
  * tdp_e4m3_to_f32:   dst[i] = value of codes[i] (dev bytes -> dev fp32), through the conversion

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtdp.so")
 SCHED_LIB = os.path.join(HERE, "libtdp_sched.so")
-SOURCES = ("gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "probe.hip")
+SOURCES = ("gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "probe.hip", "gemm_static.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

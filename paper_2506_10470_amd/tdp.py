@@ -70,6 +70,7 @@ _SIGS = {
     "tdp_stage_set_layer_range": (C.c_int, [_vp, _i32, _i32]),
     "tdp_stage_set_decode_span": (C.c_int, [_vp, _i32]),
     "tdp_gemm_bf16": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "tdp_gemm_bf16_static": (C.c_int, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp]),
     "tdp_e4m3_from_f32": (C.c_int, [_vp, _vp, _i64, C.c_float, _vp]),
     "tdp_e4m3_to_f32": (C.c_int, [_vp, _vp, _i64, _vp]),
     "tdp_probe_hbm_read": (C.c_int, [_vp, _i64, _i32, _i32, C.POINTER(_i64), C.POINTER(C.c_float), _vp]),
@@ -182,6 +183,11 @@ def tdp_stage_set_decode_span(st, span_tokens: int) -> None:
 def tdp_gemm_bf16(A, W, residual, out, M, N, K, epilogue=0, tile=0, splits=0, stream=None) -> None:
     _check(lib.tdp_gemm_bf16(_ptr(A), _ptr(W), _ptr(residual), _ptr(out), M, N, K, epilogue, tile, splits,
                              _stream(stream)))
+
+
+def tdp_gemm_bf16_static(A, W, residual, out, M, N, K, epilogue=0, tile=0, splits=0, stream=None) -> None:
+    _check(lib.tdp_gemm_bf16_static(_ptr(A), _ptr(W), _ptr(residual), _ptr(out), M, N, K, epilogue, tile, splits,
+                                    _stream(stream)))
 
 
 def tdp_e4m3_from_f32(src, codes, n, scale=1.0, stream=None) -> None:

@@ -75,6 +75,20 @@ def test_gemm_entry_rejects_bad_shapes():
     assert tdp.lib.tdp_gemm_bf16(None, None, None, None, 1, 64, 64, 0, 0, 0, None) == tdp.EINVAL
 
 
+def test_allocation_free_gemm_entry_checks_its_limits_before_any_gpu_work():
+    G = tdp.lib.tdp_gemm_bf16_static
+    for M, N, K, epi, tile, splits in [(-1, 64, 64, 0, 0, 0), (1, 0, 64, 0, 0, 0), (1, 64, 100, 0, 0, 0),
+                                       (1, 66, 64, 0, 0, 0), (1, 64, 64, 2, 0, 0), (1, 64, 64, 0, 17, 0),
+                                       (1, 64, 64, 0, 0, -1)]:
+        assert G(None, None, None, None, M, N, K, epi, tile, splits, None) == tdp.EINVAL
+    assert G(16, 16, None, 16, 1, 4096, 4096, 0, 0, 0, None) == tdp.EINVAL      # 16 Mi weight elements > 8 Mi
+    assert "static scratch" in tdp.last_error()
+    assert G(16, 16, None, 16, 4096, 256, 64, 0, 0, 0, None) == tdp.EINVAL      # 16 Mi floats of partials > 12 Mi
+    assert "workspace" in tdp.last_error()
+    assert G(None, None, None, None, 0, 64, 64, 0, 0, 0, None) == tdp.OK
+    assert G(None, None, None, None, 1, 64, 64, 0, 0, 0, None) == tdp.EINVAL    # null pointers
+
+
 def test_layer_range_and_timing_calls_reject_null_stage():
     assert tdp.lib.tdp_stage_set_layer_range(None, 0, 1) == tdp.EINVAL
     assert tdp.lib.tdp_stage_timing_enable(None, 1) == tdp.EINVAL
