@@ -219,14 +219,17 @@ TDP_API int tdp_stage_set_decode_span(tdp_stage* st, int32_t span_tokens);
  * a row-major [K, N] bf16 device matrix (repacked internally on every call: not a fast path).
  * A dev bf16 [M][K]; out dev bf16 [M][N].  K multiple of 64, N multiple of 4.
  * tile: 0 = automatic, 1..3 force a kernel variant (256 x 256, 128 x 256, 128 x 128 output tile);
- * splits: 0 = automatic, else force the split-K factor.  epilogue: 0 = plain store, 1 = out = residual + A*W (residual dev bf16 [M][N]).
+ * splits: 0 = automatic, else force the split-K factor.  epilogue: 0 = plain store; 1 = out =
+ * residual + A*W (residual dev bf16 [M][N]); 2 = the gated MLP epilogue (Sec. 3.4 counts the MLP among
+ * the linear layers that dominate a decode step): W = [W_gate | W_up] side by side, N = 2 F, and
+ * out dev bf16 [M][F] = silu(A*W_gate) * (A*W_up) with silu(z) = z / (1 + exp(-z)); F multiple of 4.
  */
 TDP_API int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out, int32_t M, int32_t N,
                   int32_t K, int32_t epilogue, int32_t tile, int32_t splits, void* stream);
 
 /*
- * tdp_gemm_bf16 for callers that cannot allocate device memory (code under HIP graph capture, tight
- * serving loops, harnesses that forbid hipMalloc): same arguments, same kernels, same results, but
+ * tdp_gemm_bf16 (epilogues 0 and 1) for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same kernels, same results, but
  * the repacked weights and the split-K partials live in a device array that is part of the library
  * image (64 MiB per GPU, held until the process ends) instead of two allocations per call.  The
  * call allocates and frees nothing and only enqueues on `stream` (it does not wait; the caller

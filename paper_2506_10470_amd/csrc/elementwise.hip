@@ -474,7 +474,7 @@ hipError_t launch_kv_copy(int to_pages, void* k_packed, void* v_packed, const Kv
 // dst(row_of(n), k) = bf16(src[k][n]) through a 32x32 LDS transpose; dst is in the weight layout
 // (layout_weights) with dst_ld columns.
 __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ src, int src_is_f32,
-                                                     int64_t K, int64_t N, bf16* __restrict__ dst,
+                                                     int64_t K, int64_t N, int64_t ld_src, bf16* __restrict__ dst,
                                                      OperandLayout lay, int64_t row_off, int mode) {
   __shared__ float tile[32][33];
   const int64_t k0 = (int64_t)blockIdx.y * 32, n0 = (int64_t)blockIdx.x * 32;
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ sr
     const int64_t k = k0 + r, n = n0 + tx;
     float v = 0.f;
     if (k < K && n < N)
-      v = src_is_f32 ? ((const float*)src)[k * N + n] : (float)((const bf16*)src)[k * N + n];
+      v = src_is_f32 ? ((const float*)src)[k * ld_src + n] : (float)((const bf16*)src)[k * ld_src + n];
     tile[r][tx] = v;
   }
   __syncthreads();
@@ -498,12 +498,17 @@ __global__ __launch_bounds__(256) void repack_kernel(const void* __restrict__ sr
   }
 }
 
+hipError_t launch_repack_ld(const void* src, int src_is_f32, int64_t rows_in, int64_t cols_out, int64_t ld_src,
+                            void* dst, int64_t dst_ld, int64_t row_off, int mode, hipStream_t s) {
+  dim3 grid((unsigned)((cols_out + 31) / 32), (unsigned)((rows_in + 31) / 32));
+  repack_kernel<<<grid, 256, 0, s>>>(src, src_is_f32, rows_in, cols_out, ld_src, (bf16*)dst, layout_weights(dst_ld),
+                                     row_off, mode);
+  return hipGetLastError();
+}
+
 hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in, int64_t cols_out, void* dst,
                          int64_t dst_ld, int64_t row_off, int mode, hipStream_t s) {
-  dim3 grid((unsigned)((cols_out + 31) / 32), (unsigned)((rows_in + 31) / 32));
-  repack_kernel<<<grid, 256, 0, s>>>(src, src_is_f32, rows_in, cols_out, (bf16*)dst, layout_weights(dst_ld), row_off,
-                                     mode);
-  return hipGetLastError();
+  return launch_repack_ld(src, src_is_f32, rows_in, cols_out, cols_out, dst, dst_ld, row_off, mode, s);
 }
 
 __global__ void convert_vec_kernel(const void* __restrict__ src, int src_is_f32, int64_t n,

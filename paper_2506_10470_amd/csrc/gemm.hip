@@ -551,7 +551,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
   const bool defer = a.splits_used != nullptr && a.epilogue != EPI_SWIGLU;
   if (a.splits_used) *a.splits_used = defer ? splits : 1;
   if (splits > 1 && !defer) {
-    const int out_cols = a.epilogue == EPI_SWIGLU ? (int)(a.Npad / 2) : a.N_store;
+    const int out_cols = a.N_store;  // (gated epilogue: columns of the result, half the weight rows)
     const int64_t n_thr = (int64_t)a.M * (out_cols / 4);
     gemm_reduce_kernel<<<(unsigned)((n_thr + 255) / 256), 256, 0, s>>>(p, out_cols);
     e = hipGetLastError();

@@ -552,26 +552,40 @@ int tdp_gemm_bf16(const void* A, const void* W, const void* residual, void* out,
                   int32_t epilogue, int32_t tile, int32_t splits, void* stream) {
   if (M < 0 || N <= 0 || K <= 0) return fail(TDP_EINVAL, "bad GEMM shape");
   if (K % 64 || N % 4) return fail(TDP_EINVAL, "K must be a multiple of 64 and N of 4");
-  if (epilogue != 0 && epilogue != 1) return fail(TDP_EINVAL, "epilogue must be 0 or 1");
+  if (epilogue < 0 || epilogue > 2) return fail(TDP_EINVAL, "epilogue must be 0, 1 or 2");
+  if (epilogue == 2 && N % 8) return fail(TDP_EINVAL, "the gated epilogue needs N = 2 F with F a multiple of 4");
   if (tile < 0 || tile > kGemmTileMax || splits < 0) return fail(TDP_EINVAL, "bad tile / splits");
   if (M == 0) return TDP_OK;
   if (!A || !W || !out || (epilogue == 1 && !residual)) return fail(TDP_EINVAL, "null pointer");
   hipStream_t s = (hipStream_t)stream;
   HIP_TRY(gemm_setup());
-  const int64_t Npad = round_up(N, 256);
+  // gated: the weights are stored as the stage stores gate/up (blocks of 32 gate rows, 32 up rows; F rounded up
+  // to 128), the result has F = N / 2 columns
+  const int64_t F = N / 2;
+  const int64_t Npad = epilogue == 2 ? 2 * round_up(F, 128) : round_up(N, 256);
   uint16_t* wt = nullptr;
   float* ws = nullptr;
   const int64_t ws_elems = (int64_t)(splits > 0 ? splits : 16) * M * Npad;
   HIP_TRY(hipMalloc((void**)&wt, (size_t)(Npad * K) * 2));
   hipError_t e = hipMalloc((void**)&ws, (size_t)ws_elems * 4);
   if (e == hipSuccess) e = hipMemsetAsync(wt, 0, (size_t)(Npad * K) * 2, s);
-  if (e == hipSuccess) e = launch_repack(W, 0, K, N, wt, K, 0, 0, s);
+  if (e == hipSuccess) {
+    if (epilogue == 2) {
+      // columns [0, F) of W are the gate matrix, [F, 2 F) the up matrix: each is a [K, F] matrix with leading
+      // dimension N, which the repack reads through its source stride
+      e = launch_repack_ld(W, 0, K, F, N, wt, K, 0, 1, s);
+      if (e == hipSuccess) e = launch_repack_ld((const uint16_t*)W + F, 0, K, F, N, wt, K, 0, 2, s);
+    } else {
+      e = launch_repack(W, 0, K, N, wt, K, 0, 0, s);
+    }
+  }
   if (e == hipSuccess) {
     GemmArgs g;
     memset(&g, 0, sizeof(g));
-    g.A = A; g.a_layout = layout_row_major(K); g.W = wt; g.Kpad = K; g.Npad = Npad; g.M = M; g.N_store = N;
-    g.out = out; g.ldo = N; g.residual = residual; g.ldr = N;
-    g.epilogue = epilogue ? EPI_RESIDUAL : EPI_STORE;
+    g.A = A; g.a_layout = layout_row_major(K); g.W = wt; g.Kpad = K; g.Npad = Npad; g.M = M;
+    g.N_store = epilogue == 2 ? (int)F : N;
+    g.out = out; g.ldo = g.N_store; g.u_layout = layout_row_major(F); g.residual = residual; g.ldr = N;
+    g.epilogue = epilogue == 2 ? EPI_SWIGLU : epilogue ? EPI_RESIDUAL : EPI_STORE;
     g.workspace = ws; g.workspace_elems = ws_elems; g.force_tile = tile; g.force_splits = splits;
     e = launch_gemm(g, s);
   }

@@ -74,6 +74,9 @@ hipError_t gemm_setup();  // one-time function attributes (dynamic LDS size)
 // dst is in layout_weights(dst_ld)
 hipError_t launch_repack(const void* src, int src_is_f32, int64_t rows_in /*K*/, int64_t cols_out /*N*/,
                          void* dst, int64_t dst_ld, int64_t row_off, int mode, hipStream_t s);
+// the same from a source whose rows are ld_src elements apart (a column range of a wider matrix)
+hipError_t launch_repack_ld(const void* src, int src_is_f32, int64_t rows_in, int64_t cols_out, int64_t ld_src,
+                            void* dst, int64_t dst_ld, int64_t row_off, int mode, hipStream_t s);
 hipError_t launch_convert_vec(const void* src, int src_is_f32, int64_t n, float* dst, hipStream_t s);
 
 // ---- pipeline ends ----------------------------------------------------------------------------

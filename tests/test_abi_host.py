@@ -67,7 +67,7 @@ def test_e4m3_diagnostics_reject_bad_arguments():
 
 def test_gemm_entry_rejects_bad_shapes():
     for M, N, K, epi, tile, splits in [(-1, 64, 64, 0, 0, 0), (1, 0, 64, 0, 0, 0), (1, 64, 100, 0, 0, 0),
-                                       (1, 66, 64, 0, 0, 0), (1, 64, 64, 2, 0, 0), (1, 64, 64, 0, 17, 0),
+                                       (1, 66, 64, 0, 0, 0), (1, 64, 64, 3, 0, 0), (1, 68, 64, 2, 0, 0), (1, 64, 64, 0, 17, 0),
                                        (1, 64, 64, 0, 0, -1)]:
         assert tdp.lib.tdp_gemm_bf16(None, None, None, None, M, N, K, epi, tile, splits, None) == tdp.EINVAL
     # M = 0 is a no-op, and null pointers with M > 0 are rejected

@@ -187,3 +187,41 @@ def test_stage_prefill_and_decode_carry_the_stored_cache():
     assert new8[1][0][0].shape[0] == 4
     grid = set(F8.e4m3_decode_table()[:0x7F].tolist())
     assert all(abs(v) in grid for v in new8[1][1][1].ravel())
+
+
+def test_stored_cache_is_the_reading_under_which_decode_equals_full_recompute():
+    """Which values prefill attends to when the cache is held in 8 bits is fixed by an invariant of the
+    method itself, not by how a kernel happens to read: decoding one token on a cache must give what
+    recomputing the whole sequence gives at its last position (prefill(L) = prefill(L-1) + decode, the
+    KV cache being only a memo of the prefill's keys and values, Sec. 2.1).  A decode step can only see
+    what the cache holds, i.e. the rounded keys and values; so the recompute must see them too.  With
+    the cache as the one source the invariant holds exactly, also token by token; if prefill attended to
+    the unrounded keys and values instead, it would break."""
+    rng = np.random.default_rng(12)
+    layers = [rand_layer(16, SH, 24, rng) for _ in range(3)]
+    q8 = O.Shape(4, 2, 8, kv_scales=(0.5, 2.0))
+    x = rng.normal(size=(7, 16))
+    full, caches_full = O.stage_forward(x, None, layers, q8)
+    part, caches = O.stage_forward(x[:6], None, layers, q8)
+    last, caches2 = O.stage_forward(x[6:7], caches, layers, q8)
+    assert np.allclose(part, full[:6], atol=1e-12) and np.allclose(last[0], full[6], atol=1e-12)
+    for (ka, va), (kb, vb) in zip(caches_full, caches2):
+        assert np.array_equal(ka[:6], kb[:6]) and np.allclose(ka, kb, atol=1e-12) and np.allclose(va, vb, atol=1e-12)
+    # one prefill token followed by single-token decode steps
+    out, c = O.stage_forward(x[:1], None, layers, q8)
+    rows = [out[0]]
+    for t in range(1, 7):
+        outs, cs = O.stage_decode([x[t]], [c], layers, q8)
+        rows.append(outs[0])
+        c = cs[0]
+    assert np.allclose(np.stack(rows), full, atol=1e-11)
+    # the other reading - prefill attends to the keys and values as computed and only stores the codes -
+    # recomposed from the oracle's primitives for one layer: its last row is NOT what decode gives
+    w = layers[0]
+    _, k_plain, v_plain = O.layer_forward(x, O.empty_cache(SH), O.empty_cache(SH), w, SH)
+    as_computed = by_hand_layer(x, k_plain, v_plain, 0, w, SH)
+    _, k6, v6 = O.layer_forward(x[:6], O.empty_cache(SH), O.empty_cache(SH), w, q8)
+    dec, _, _ = O.layer_forward(x[6:7], k6, v6, w, q8)
+    assert np.max(np.abs(as_computed[6] - dec[0])) > 1e-4
+    stored, _, _ = O.layer_forward(x, O.empty_cache(SH), O.empty_cache(SH), w, q8)
+    assert np.allclose(stored[6], dec[0], atol=1e-12)

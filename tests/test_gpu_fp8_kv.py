@@ -26,6 +26,7 @@ pytestmark = pytest.mark.gpu
 
 STEP = 2.0 ** -3        # largest relative distance between neighbouring E4M3 values
 SHORT_CTX = 15
+EQUAL_CODES = []        # fraction of equal codes of every stored token that was checked (printed at the end)
 
 
 @pytest.fixture(scope="module")
@@ -189,7 +190,18 @@ def check_stored_token(hip_codes, pre, scale, what):
     # bf16 error of the sum that produced them is not) may differ by that error instead
     small = np.abs(got - want) <= 2.0 ** -7 * np.max(np.abs(want), axis=-1, keepdims=True)
     assert np.all((d <= 1) | small), (what, "codes more than one step apart", int(np.max(d)))
-    assert np.mean(d == 0) >= 0.75, (what, "too many neighbouring codes", float(np.mean(d == 0)))
+    # How often the two sides may differ.  The stage's number carries the error of a bf16-operand
+    # projection: about 2^-9 / sqrt(3) = 1.1e-3 of the row's rms r (each input is rounded to 8 significant
+    # bits, the sum is fp32), plus, for values, their own rounding to bf16 (at most 2^-9 of the element).
+    # A rounding boundary falls between the two numbers with probability |error| / step, and the steps of
+    # the format are 1/16 to 1/8 of the element: about 1 % for an element as large as r, growing as
+    # r / |element| below it; averaged over normally distributed elements 4 to 6 %.  One token's entries
+    # (64 to 1024 of them) are held to that rate plus four standard deviations of a binomial count; all
+    # tokens of a run together to 93 % equal codes (test_zz_equal_code_fraction_over_the_run).
+    EQUAL_CODES.append((int(np.sum(d == 0)), int(d.size)))
+    n_el, p_flip = d.size, 0.06
+    allowed = n_el * p_flip + 4.0 * np.sqrt(n_el * p_flip * (1.0 - p_flip)) + 1.0
+    assert np.sum(d != 0) <= allowed, (what, "too many neighbouring codes", int(np.sum(d != 0)), n_el)
     # Where the oracle's number is further from both neighbouring boundaries than the bf16 error of the
     # stage's own number, the code is decided and must be the same.  That error: the projection is
     # stored in bf16 (2^-9 of the element), the rotation mixes two such entries (2^-9 of the row
@@ -202,8 +214,9 @@ def check_stored_token(hip_codes, pre, scale, what):
     decided = dist > margin
     assert decided.mean() > 0.1, what        # the check must not be vacuous
     assert np.array_equal(np.asarray(hip_codes)[decided], ref[decided]), what
-    # and the stored values are within one step plus the tolerance of the oracle's stored values
-    assert np.all(row_errs(got, want) <= TOL + STEP), what
+    # and the stored values are within one step of the oracle's stored values (a step is at most 2^-3 of the
+    # element, hence of the row maximum)
+    assert np.all(row_errs(got, want) <= STEP), what
 
 
 def run_decode_case(tdp, shape_name, ctx_lens, scales, n_layers=None, stream_id=1, max_pages_per_seq=None, span=0):
@@ -424,3 +437,15 @@ def test_decode_is_invariant_under_block_table_permutation(tdp):
             torch.cuda.synchronize()
             outs.append(out.view(torch.int16).cpu())
     assert torch.equal(outs[0], outs[1])
+
+
+def test_zz_equal_code_fraction_over_the_run():
+    """Over every stored token the tests above looked at, the stage and the oracle stored the same code for
+    at least 93 % of the entries (expected from the projection's bf16 operand error: 94 to 96 %)."""
+    import sys
+    if not EQUAL_CODES:
+        pytest.skip("no stored token was checked in this run")
+    same, total = sum(a for a, _ in EQUAL_CODES), sum(b for _, b in EQUAL_CODES)
+    print("equal codes, stage vs oracle: %.4f of %d entries in %d stored tokens" % (same / total, total, len(EQUAL_CODES)),
+          file=sys.stderr, flush=True)
+    assert same / total >= 0.93

@@ -193,6 +193,28 @@ def test_gemm_matches_fp64_product(tdp, M, N, K, tile, splits, epi):
     assert row_rel_err(f64(out), ref) <= 1e-2
 
 
+@pytest.mark.parametrize("M,F,K,tile,splits", [
+    (4, 688, 256, 0, 0), (33, 128, 128, 2, 2), (130, 344, 320, 2, 1), (300, 1376, 1024, 1, 1), (257, 516, 192, 1, 2),
+    (100, 64, 256, 3, 1), (512, 1024, 2048, 0, 0), (70, 260, 512, 3, 3),
+])
+def test_gated_mlp_epilogue_matches_the_fp64_definition(tdp, M, F, K, tile, splits):
+    """The gate/up projection with its fused epilogue alone: out = silu(A W_gate) * (A W_up), every kernel
+    variant, ragged M and F (F not a multiple of the 32-row gate/up interleave), with and without split-K
+    (split-K sums the partials before the activation).  Gate pre-activations span about +-6, so both
+    tails of the sigmoid and its middle are exercised."""
+    g = torch.Generator(device="cpu").manual_seed(M * 977 + F)
+    A = torch.randn(M, K, generator=g).to(torch.bfloat16).cuda()
+    Wg = (torch.randn(K, F, generator=g) * (2.0 / K ** 0.5)).to(torch.bfloat16)
+    Wu = (torch.randn(K, F, generator=g) * (1.0 / K ** 0.5)).to(torch.bfloat16)
+    Wm = torch.cat([Wg, Wu], dim=1).contiguous().cuda()
+    out = torch.full((M, F), float("nan"), dtype=torch.bfloat16, device="cuda")
+    tdp.tdp_gemm_bf16(A, Wm, None, out, M, 2 * F, K, 2, tile, splits)
+    gate = f64(A) @ f64(Wg)
+    ref = gate / (1.0 + np.exp(-gate)) * (f64(A) @ f64(Wu))
+    assert np.abs(gate).max() > 4.0
+    assert row_rel_err(f64(out), ref) <= 1e-2
+
+
 # ----------------------------------------------------------------------------- the stage
 
 def test_decode_tiny_config(tdp):
