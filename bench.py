@@ -84,7 +84,16 @@ def step_percentiles(fn, steps):
     torch.cuda.synchronize()
     t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
     pick = lambda q: round(t[min(len(t) - 1, int(q * len(t)))], 4)
-    return {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90), "steps": steps}
+    return {"p10": pick(0.10), "p50": pick(0.50), "p90": pick(0.90), "mean": round(sum(t) / len(t), 4), "steps": steps}
+
+
+def time_events(fn, warmup, steps):
+    """Mean and p10 / p50 / p90 of single calls, from events on the launch stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    pct = step_percentiles(fn, steps)
+    return pct
 
 
 def class_times(tdp, st, fn, reps):
@@ -133,20 +142,26 @@ def kernel_rooflines(shape, M, kv_read_bytes, attn_flops, times_ms, phase):
     return res
 
 
+TRAFFIC_FILES = {"70b_quarter stage, decode phase, batch 512": "traffic_decode_70b_quarter_b512.json",
+                 "70b_quarter stage, decode phase, batch 256": "traffic_decode_70b_quarter_b256.json"}
+
+
 def measured_traffic(workload):
-    """HBM bytes per launch measured with rocprofv3 TCC counters (committed under profiles/, see the
-    summary there for the commands); None when no measurement exists for this workload."""
-    path = os.path.join(ROOT, "profiles", "traffic_decode_70b_quarter_b512.json")
+    """HBM bytes per launch measured with rocprofv3 TCC counters in an EARLIER run (committed under
+    profiles/, see the summary there for the commands): rocprofv3 cannot run inside this process, so the
+    figure is a stored one.  Returns (per-class bytes, description of where they come from)."""
+    name = TRAFFIC_FILES.get(workload)
+    if not name:
+        return {}, None
     try:
-        t = json.load(open(path))
+        t = json.load(open(os.path.join(ROOT, "profiles", name)))
     except OSError:
-        return {}
-    if t.get("workload") != workload:
-        return {}
+        return {}, None
     per = t["per_launch"]
     tot = lambda *ks: sum(per[k]["fetch_bytes"] + per[k]["write_bytes"] for k in ks if k in per)
+    src = "stored, not measured in this run: profiles/%s (%s; recorded %s)" % (name, t.get("source", "?"), t.get("recorded", "?"))
     return {"attention": tot("attn_decode_kernel", "attn_decode_merge_kernel"), "gemm_qkv": tot("gemm_qkv"),
-            "gemm_o": tot("gemm_o"), "gemm_gate_up": tot("gemm_gate_up"), "gemm_down": tot("gemm_down")}
+            "gemm_o": tot("gemm_o"), "gemm_gate_up": tot("gemm_gate_up"), "gemm_down": tot("gemm_down")}, src
 
 
 def cpu_baseline(shape, dec_ctx, cu, budget_layers=4, n_requests=64):
@@ -194,6 +209,38 @@ def cpu_baseline(shape, dec_ctx, cu, budget_layers=4, n_requests=64):
                       "layers; input preparation %.1f s not timed" % (
                           len(sample), min(int(dec_ctx[b]) for b in sample), max(int(dec_ctx[b]) for b in sample),
                           float(np.mean([dec_ctx[b] for b in sample])), budget_layers, shape.n_layers, dt, t_prep)}
+
+
+def micro_batch_section(tdp, W, Stage, shape, dec_ctx, i32, steps, warmup):
+    """The headline decode step as two half-batches on two streams (decode_micro_batches = 2), same weights,
+    same cache contents; an option of the library, measured beside the one-batch form."""
+    import torch
+    B = len(dec_ctx)
+    max_pps = 4096 // 16 + 2
+    dec = W.make_decode_batch(dec_ctx, max_pages_per_seq=max_pps, steps=ADVANCE_STEPS + 1)
+    st = Stage(tdp, shape, dec.num_pages, B, 0, 0, max_pps, load_weights=True, decode_micro_batches=2)
+    total = int(dec_ctx.sum())
+    cu = np.zeros(B + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(dec_ctx)
+    cu_d, tab_d = i32(cu), i32(dec.tables)
+    for l in range(shape.n_layers):
+        k = W.kv_packed(shape, l, "k", total, 1, device="cuda")
+        v = W.kv_packed(shape, l, "v", total, 1, device="cuda")
+        tdp.tdp_stage_kv_import(st.h, l, k, v, cu_d, tab_d, B, total)
+        torch.cuda.synchronize()
+        del k, v
+    stream = torch.cuda.current_stream()
+    x = W.hidden_states(shape, B, 1, device="cuda")
+    out = torch.empty_like(x)
+    ctx_d = i32(dec.ctx_lens)
+    res = {"decode_micro_batches": 2, "batches": []}
+    for b in (B, B // 2):
+        pb = time_events(lambda: tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, b, out, stream), warmup, max(steps, 20))
+        res["batches"].append({"batch": b, "ms_per_step": pb["mean"], "ms_p10": pb["p10"], "ms_p90": pb["p90"],
+                               "tok_s": round(b / pb["mean"] * 1e3, 1)})
+    st.close()
+    torch.cuda.empty_cache()
+    return res
 
 
 def fp8_kv_section(tdp, W, Stage, A, shape, sargs, dec_ctx, i32, steps, warmup):
@@ -364,6 +411,61 @@ def scheduler_section(shape, decode_sweep, prefill_curve, n_requests=20000, n_st
             "memory_tight": {"kv_capacity_tokens": capacity // 4, "policies": run_policies(capacity // 4)}}
 
 
+def other_config_section(tdp, W, Stage, A, i32, name, batches, n_prompts):
+    """A lean pass over one of the other benchmark configurations (same code paths as the headline): decode
+    at the given batch sizes, timed per step with events, per-class times and rooflines at the largest,
+    and the configuration's prefill batch."""
+    import torch
+    shape = W.SHAPES[name]
+    B = max(batches)
+    dec_ctx = W.decode_ctx_lens(name, B)
+    pre_lens = W.prefill_seq_lens(name, n_prompts)
+    st, dec, pre, pre_tables, _ = build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32)
+    stream = torch.cuda.current_stream()
+    sargs = (shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff)
+    x = W.hidden_states(shape, B, 1, device="cuda")
+    out = torch.empty_like(x)
+    ctx_d, tab_d = i32(dec.ctx_lens), i32(dec.tables)
+    fn = lambda b=B: tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, b, out, stream)
+    sweep = []
+    for b in batches:
+        pb = time_events(lambda: fn(b), 5, 30)
+        wb = A.decode_step_work(*sargs, dec_ctx[:b])
+        sweep.append({"batch": b, "ms_per_step": pb["mean"], "ms_p10": pb["p10"], "ms_p90": pb["p90"],
+                      "tok_s": round(b / pb["mean"] * 1e3, 1), "hbm_gbs": round(wb["bytes"] / pb["mean"] / 1e6, 1),
+                      "hbm_frac": round(wb["bytes"] / pb["mean"] / 1e6 / HBM_PEAK_GBS, 4)})
+    peak = max(v["tok_s"] for v in sweep)
+    for v in sweep:
+        v["spatial_intensity"] = round(v["tok_s"] / peak, 4)
+    work = A.decode_step_work(*sargs, dec_ctx)
+    ct = class_times(tdp, st, fn, 3)
+    kern = kernel_rooflines(shape, B, work["kv_read_bytes"], work["attn_flops"], ct, "decode")
+    T = int(pre_lens.sum())
+    xp = W.hidden_states(shape, T, 2, device="cuda")
+    op = torch.empty_like(xp)
+    cu_p, tab_p = i32(pre.cu_seqlens), i32(pre_tables)
+    pfn = lambda: tdp.tdp_stage_prefill(st.h, xp, cu_p, tab_p, len(pre_lens), T, op, stream)
+    msp = time_calls(pfn, 1, 3)
+    wp = A.prefill_work(*sargs, pre_lens)
+    ctp = class_times(tdp, st, pfn, 2)
+    gemm_ms = sum(ctp[k] for k in ("gemm_qkv", "gemm_o", "gemm_gate_up", "gemm_down"))
+    res = {"workload": "%s stage" % name, "n_layers": shape.n_layers, "mean_ctx": round(float(dec_ctx.mean()), 1),
+           "decode_sweep": sweep,
+           "decode_at_batch_%d" % B: {"class_ms": {k: round(v, 4) for k, v in ct.items()}, "kernels": kern},
+           "prefill": {"tokens": T, "n_prompts": len(pre_lens), "ms": round(msp, 3), "tok_s": round(T / msp * 1e3, 1),
+                       "tflops": round(wp["flops"] / msp / 1e9, 1),
+                       "gemm_tflops": round(wp["gemm_flops"] / gemm_ms / 1e9, 1),
+                       "gemm_mfma_frac": round(wp["gemm_flops"] / gemm_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                       "class_ms": {k: round(v, 3) for k, v in ctp.items()}}}
+    log("%s: decode %s; prefill %d tokens %.1f ms (GEMMs %.0f TFLOP/s)" % (
+        name, ", ".join("B=%d %.2f ms %.0f GB/s" % (v["batch"], v["ms_per_step"], v["hbm_gbs"]) for v in sweep), T, msp,
+        wp["gemm_flops"] / gemm_ms / 1e9))
+    del xp, op, x, out
+    st.close()
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -375,6 +477,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--micro-batches", type=int, default=0, choices=[0, 2],
+                    help="2: also time the headline step as two half-batches on two streams (decode_micro_batches)")
+    ap.add_argument("--no-others", action="store_true", help="skip the lean passes over the other configurations")
     ap.add_argument("--kv-fp8", action="store_true",
                     help="run the 8-bit KV-cache section even in the lean (--no-sweep) mode")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -426,7 +531,9 @@ def main():
                                                                           work["bytes"] / ms / 1e6))
     pct, ms_adv = None, None
     if not args.no_sweep:   # (--no-sweep is the lean mode the profiler runs use: headline + per-class times only)
-        pct = step_percentiles(decode_fn, max(args.steps, 20))
+        for _ in range(max(0, 20 - args.warmup - args.steps)):   # at least 20 steps before the percentiles
+            decode_fn()
+        pct = step_percentiles(decode_fn, max(args.steps, 100))
         # the same step repeated rewrites the same KV slot; this run advances every context by one token
         # per step instead, so each request crosses a page boundary once within ADVANCE_STEPS steps
         ctx_run = ctx_d.clone()
@@ -439,9 +546,11 @@ def main():
     ct = class_times(tdp, st, decode_fn, 5)
     kern = kernel_rooflines(shape, B, work["kv_read_bytes"], work["attn_flops"], ct, "decode")
     workload_name = "%s stage, decode phase, batch %d" % (args.workload, B)
-    for name, tr in measured_traffic(workload_name).items():
+    traffic, traffic_src = measured_traffic(workload_name)
+    for name, tr in traffic.items():
         if name in kern and not args.layers:
             kern[name]["traffic"] = tr
+            kern[name]["traffic_source"] = traffic_src
     dominant = max(kern, key=lambda k: ct[k])
     roof = dict(kern[dominant])
     roof["kernel"] = dominant
@@ -475,16 +584,37 @@ def main():
         for b in (16, 32, 64, 128, 256, 512):
             if b > B:
                 continue
-            msb = time_calls(lambda: decode_fn(b), 3, 10)
+            pb = time_events(lambda: decode_fn(b), 5, 40)       # events on the launch stream, per step
+            msb = pb["mean"]
             wb = A.decode_step_work(*sargs, dec_ctx[:b])
-            sweep.append({"batch": b, "ms_per_step": round(msb, 4), "tok_s": round(b / msb * 1e3, 1),
-                          "hbm_gbs": round(wb["bytes"] / msb / 1e6, 1),
+            sweep.append({"batch": b, "ms_per_step": round(msb, 4), "ms_p10": pb["p10"], "ms_p90": pb["p90"],
+                          "tok_s": round(b / msb * 1e3, 1), "hbm_gbs": round(wb["bytes"] / msb / 1e6, 1),
                           "hbm_frac": round(wb["bytes"] / msb / 1e6 / HBM_PEAK_GBS, 4)})
             log("  sweep B=%d: %.3f ms, %.0f tok/s, %.0f GB/s" % (b, msb, b / msb * 1e3, wb["bytes"] / msb / 1e6))
         peak = max(s["tok_s"] for s in sweep)
         for s in sweep:
             s["spatial_intensity"] = round(s["tok_s"] / peak, 4)     # Achieved / Peak (paper Eq. 1)
         result["decode_sweep"] = sweep
+        # the batch the HBM target is stated on (>= 256): per-kernel rooflines of the same stage at batch 256
+        if B > 256:
+            b = 256
+            w256 = A.decode_step_work(*sargs, dec_ctx[:b])
+            ct256 = class_times(tdp, st, lambda: decode_fn(b), 5)
+            k256 = kernel_rooflines(shape, b, w256["kv_read_bytes"], w256["attn_flops"], ct256, "decode")
+            tr256, src256 = measured_traffic("%s stage, decode phase, batch %d" % (args.workload, b))
+            for name, tr in tr256.items():
+                if name in k256 and not args.layers:
+                    k256[name]["traffic"] = tr
+                    k256[name]["traffic_source"] = src256
+            ms256 = next(x["ms_per_step"] for x in sweep if x["batch"] == b)
+            t_min256 = sum(max(v["alg_bytes_per_launch"] * v["launches_per_step"] / (HBM_PEAK_GBS * 1e9),
+                               v["alg_flops_per_launch"] * v["launches_per_step"] / (MFMA_BF16_PEAK_TFLOPS * 1e12))
+                           for v in k256.values()) * 1e3
+            result["decode_b256"] = {"batch": b, "ms_per_step": ms256, "tok_s": round(b / ms256 * 1e3, 1),
+                                     "alg_bytes_per_step": w256["bytes"], "hbm_gbs": round(w256["bytes"] / ms256 / 1e6, 1),
+                                     "hbm_frac": round(w256["bytes"] / ms256 / 1e6 / HBM_PEAK_GBS, 4),
+                                     "composite_t_min_ms": round(t_min256, 3), "composite_frac": round(t_min256 / ms256, 4),
+                                     "class_ms": {k: round(v, 4) for k, v in ct256.items()}, "kernels": k256}
 
     # ---- prefill
     if not args.no_prefill:
@@ -539,6 +669,9 @@ def main():
         log("empirical ceilings: %s" % json.dumps(emp))
     st.close()
     torch.cuda.empty_cache()
+    if args.micro_batches == 2:
+        result["decode_two_half_batches"] = micro_batch_section(tdp, W, Stage, shape, dec_ctx, i32, args.steps, args.warmup)
+        log("decode as two half-batches on two streams: %s" % json.dumps(result["decode_two_half_batches"]["batches"]))
     if args.kv_fp8 or not (args.layers or args.no_sweep):
         result["decode_fp8_kv"] = fp8_kv_section(tdp, W, Stage, A, shape, sargs, dec_ctx, i32, args.steps, args.warmup)
         log("decode B=%d with an 8-bit KV cache: %.3f ms/step, %.0f tok/s (attention %.3f ms per step)" % (
@@ -559,6 +692,12 @@ def main():
             result["engine"]["n_requests"], json.dumps({k: result["engine"][k] for k in (
                 "generated_tokens", "decode_steps", "prefill_batches", "phase_switches", "recomputes",
                 "wall_s_one_gpu_sequential", "tok_s_one_gpu_sequential")})))
+    if args.workload == "70b_quarter" and not (args.layers or args.no_sweep or args.no_others):
+        # the other benchmark configurations (7B decode at batch 256 + prefill; 13B prefill and batch sweep, the
+        # Achieved / Peak curve of Sec. 3.5 on the paper's own 13B shape), lean passes through the same code
+        result["other_configs"] = {
+            "7b_quarter": other_config_section(tdp, W, Stage, A, i32, "7b_quarter", (256,), 32),
+            "13b_quarter": other_config_section(tdp, W, Stage, A, i32, "13b_quarter", (16, 32, 64, 128, 256, 512), 32)}
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(shape, dec_ctx, cu)
         log("cpu oracle: %s tok/s (%s)" % (result["cpu_baseline"]["value"], result["cpu_baseline"]["sample"]))

@@ -27,7 +27,7 @@ def dev_view_u8(ptr: int, nbytes: int) -> torch.Tensor:
 class Stage:
     def __init__(self, tdp, shape: W.StageShape, num_pages: int, max_batch: int, max_tokens: int,
                  max_seqs: int, max_pages_per_seq: int, weight_dtype=torch.bfloat16, load_weights=True,
-                 kv_scales=None, layer_offset: int = 0):
+                 kv_scales=None, layer_offset: int = 0, decode_micro_batches: int = 0):
         """kv_scales: None = bf16 KV pools; (k_scale, v_scale) = 8-bit (E4M3) pools with those scales.
         layer_offset: the stage's layer l gets the generated weights of model layer layer_offset + l (a
         later stage of a pipeline)."""
@@ -41,7 +41,8 @@ class Stage:
             rope_base=shape.rope_base, page_size=shape.page_size, num_pages=num_pages, max_batch=max_batch,
             max_tokens=max_tokens, max_seqs=max_seqs, max_pages_per_seq=max_pages_per_seq,
             kv_dtype=tdp.KV_BF16 if kv_scales is None else tdp.KV_FP8_E4M3,
-            k_scale=0.0 if kv_scales is None else kv_scales[0], v_scale=0.0 if kv_scales is None else kv_scales[1])
+            k_scale=0.0 if kv_scales is None else kv_scales[0], v_scale=0.0 if kv_scales is None else kv_scales[1],
+            decode_micro_batches=decode_micro_batches)
         self.h = tdp.tdp_stage_create(self.cfg)
         self.num_pages = num_pages
         self.max_pages_per_seq = max_pages_per_seq

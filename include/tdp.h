@@ -93,6 +93,16 @@ typedef struct tdp_stage_config {
    * is otherwise unchanged.  k_scale / v_scale: per stage, > 0; 0 means 1. */
   int32_t kv_dtype;
   float   k_scale, v_scale;
+  /* Decode batches as two half-batches on two streams (0 or 1: off, the default; 2: on).  The decode
+   * phase alternates a step bound by reading the cache (attention) with steps bound by the matrix
+   * cores (the projections, Sec. 2.1 and Sec. 3.4); with two half-batches in flight one half's attention
+   * may run beside the other half's projections.  The stage then holds a second set of scratch buffers
+   * and a second stream of its own (default priority); tdp_stage_decode forks it behind the work already
+   * queued on the caller's stream and joins it before returning control of that stream, so callers see
+   * the same semantics (graph capture included).  Results equal the one-batch form's within rounding;
+   * per-class timing is not recorded in this form.  Measured slower than one batch on MI355X at the
+   * benchmark shapes (each half streams all weights again): an option, not the default. */
+  int32_t decode_micro_batches;
 } tdp_stage_config;
 
 /* Version of this ABI (bumped on incompatible change). */

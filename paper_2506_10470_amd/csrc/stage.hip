@@ -52,15 +52,23 @@ struct tdp_stage {
   int64_t pool_elems = 0;  // per layer, per pool
   int64_t pool_bytes = 0;  // pool_elems * (2: bf16 | 1: E4M3 codes)
   float k_scale = 1.f, v_scale = 1.f;
-  uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *u = nullptr;  // bf16 activations
-  float* qkv32 = nullptr;  // the QKV projection as the GEMM leaves it (fp32): rotated before its one rounding
-  float *h = nullptr, *xa = nullptr, *xb = nullptr;  // residual stream, fp32 between layers
-  float* ws = nullptr;
+  // Everything one pass over a batch writes besides the KV pools.  A stage that runs decode batches as two
+  // half-batches on two streams (decode_micro_batches = 2) holds two sets.
+  struct Scratch {
+    uint16_t *y = nullptr, *qkv = nullptr, *attn = nullptr, *u = nullptr;  // bf16 activations
+    float* qkv32 = nullptr;  // the QKV projection as the GEMM leaves it (fp32): rotated before its one rounding
+    float *h = nullptr, *xa = nullptr, *xb = nullptr;  // residual stream, fp32 between layers
+    float* ws = nullptr;
+    float *part_o = nullptr, *part_ml = nullptr;
+    int4* attn_items = nullptr;     // decode work list, rebuilt every step
+    int32_t* attn_n_items = nullptr;
+    int32_t* attn_item_pages = nullptr;  // physical pages of every item's span
+  };
+  Scratch sc[2];
+  int n_scratch = 1;
+  hipStream_t aux_stream = nullptr;             // second half-batch (default priority)
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   int64_t ws_elems = 0;
-  float *part_o = nullptr, *part_ml = nullptr;
-  int4* attn_items = nullptr;     // decode work list, rebuilt every step
-  int32_t* attn_n_items = nullptr;
-  int32_t* attn_item_pages = nullptr;  // physical pages of every item's span
   int max_chunks = 0;             // spans of kDecodeSpanMin tokens in the longest context
   float2* rope_table = nullptr;
   int32_t *check_owner = nullptr, *check_res = nullptr;  // scratch of the table checks
@@ -94,6 +102,8 @@ int check_config(const tdp_stage_config* c) {
     return fail(TDP_EINVAL, "max_seqs must be >= 1 when max_tokens > 0");
   if (c->max_pages_per_seq < 1) return fail(TDP_EINVAL, "max_pages_per_seq must be >= 1");
   if ((int64_t)c->max_pages_per_seq * 16 > (1 << 20)) return fail(TDP_EINVAL, "max_pages_per_seq too large");
+  if (c->decode_micro_batches < 0 || c->decode_micro_batches > 2)
+    return fail(TDP_EINVAL, "decode_micro_batches must be 0, 1 or 2");
   if (c->kv_dtype != TDP_KV_BF16 && c->kv_dtype != TDP_KV_FP8_E4M3)
     return fail(TDP_EINVAL, "kv_dtype must be TDP_KV_BF16 or TDP_KV_FP8_E4M3");
   if (c->kv_dtype == TDP_KV_FP8_E4M3) {
@@ -116,7 +126,7 @@ struct Timer {
   tdp_stage* st;
   hipStream_t s;
   bool on;
-  Timer(tdp_stage* st_, hipStream_t s_, int cls) : st(st_), s(s_), on(st_->timing) {
+  Timer(tdp_stage* st_, hipStream_t s_, bool timed, int cls) : st(st_), s(s_), on(st_->timing && timed) {
     if (!on) return;
     if (st->ev_used == st->ev_start.size()) {
       hipEvent_t a, b;
@@ -153,11 +163,12 @@ KvLayout kv_layout(tdp_stage* st, int layer) {
 }
 
 // The layer sequence shared by both phases.  M tokens; decode when ctx_lens != null.
-int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, const int32_t* ctx_lens,
-               const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables, hipStream_t s) {
+int run_layers(tdp_stage* st, tdp_stage::Scratch& sc, bool timed, const void* hidden_in, void* hidden_out, int M,
+               const int32_t* ctx_lens, const int32_t* cu_seqlens, int n_seqs, const int32_t* block_tables,
+               hipStream_t s) {
   const tdp_stage_config& c = st->cfg;
   const int64_t d = c.d_model;
-  st->ev_used = 0;
+  if (timed) st->ev_used = 0;
   // The residual stream enters and leaves the stage as bf16 (the pipeline's hand-over format) and
   // is kept in fp32 in between: two bf16 roundings per layer would otherwise pile up over a
   // 20-layer stage to more than the 2e-2 parity bound.
@@ -165,8 +176,8 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
   int x_f32 = 0;
   const int span_len = st->decode_span > 0 ? st->decode_span : attn_decode_span(M, c.n_kv_heads);
   if (ctx_lens)
-    HIP_TRY(launch_attn_plan(ctx_lens, block_tables, c.max_pages_per_seq, M, st->max_chunks, span_len, st->attn_items,
-                             st->attn_n_items, st->attn_item_pages, s));
+    HIP_TRY(launch_attn_plan(ctx_lens, block_tables, c.max_pages_per_seq, M, st->max_chunks, span_len, sc.attn_items,
+                             sc.attn_n_items, sc.attn_item_pages, s));
   const int l_begin = st->layer_count > 0 ? st->layer_first : 0;
   const int l_end = st->layer_count > 0 ? st->layer_first + st->layer_count : c.n_layers;
   // A projection whose K range was split leaves fp32 partials in the workspace; the kernel that
@@ -178,26 +189,26 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
   for (int l = l_begin; l < l_end; ++l) {
     const KvLayout kv = kv_layout(st, l);
     const bool last = l == l_end - 1;
-    void* x_next = last ? hidden_out : (void*)((l & 1) ? st->xb : st->xa);
+    void* x_next = last ? hidden_out : (void*)((l & 1) ? sc.xb : sc.xa);
     {  // a1: pre-attention RMSNorm
-      Timer t(st, s, T_NORM);
+      Timer t(st, s, timed, T_NORM);
       if (down_splits > 1)
-        HIP_TRY(launch_rmsnorm_sum(st->h, 1, d, st->ws, down_splits, st->d_pad, (float*)const_cast<void*>(x), d,
-                                   st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, layout_paired(d), s));
+        HIP_TRY(launch_rmsnorm_sum(sc.h, 1, d, sc.ws, down_splits, st->d_pad, (float*)const_cast<void*>(x), d,
+                                   st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, sc.y, layout_paired(d), s));
       else
-        HIP_TRY(launch_rmsnorm(x, x_f32, d, st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, layout_paired(d), s));
+        HIP_TRY(launch_rmsnorm(x, x_f32, d, st->g_attn + (int64_t)l * d, c.rms_eps, M, (int)d, sc.y, layout_paired(d), s));
     }
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     int qkv_splits = 1, o_splits = 1;
-    g.workspace = st->ws;
+    g.workspace = sc.ws;
     g.workspace_elems = st->ws_elems;
     g.M = M;
     {  // a2: fused QKV projection
-      Timer t(st, s, T_QKV);
-      g.A = st->y; g.a_layout = layout_paired(d);
+      Timer t(st, s, timed, T_QKV);
+      g.A = sc.y; g.a_layout = layout_paired(d);
       g.W = st->wqkv + (int64_t)l * st->Nqkv_pad * d; g.Kpad = d; g.Npad = st->Nqkv_pad;
-      g.N_store = (int)st->Nqkv_pad; g.out = st->qkv32; g.ldo = st->Nqkv_pad;
+      g.N_store = (int)st->Nqkv_pad; g.out = sc.qkv32; g.ldo = st->Nqkv_pad;
       g.residual = nullptr; g.ldr = 0; g.epilogue = EPI_STORE; g.out_f32 = 1; g.residual_f32 = 0;
       g.bias = st->has_bias ? st->bqkv + (int64_t)l * st->Nqkv_pad : nullptr;
       g.splits_used = fuse_reduce ? &qkv_splits : nullptr;
@@ -206,55 +217,55 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
     }
     {  // a3: rotary embedding + KV append, from the fp32 projection (if it was split: sums the partials and
        // adds the bias, which the GEMM's epilogue has done otherwise)
-      Timer t(st, s, T_ROPE);
+      Timer t(st, s, timed, T_ROPE);
       const bool split = qkv_splits > 1;
-      HIP_TRY(launch_rope_kv(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, st->rope_table, st->max_pos, ctx_lens,
-                             cu_seqlens, n_seqs, block_tables, c.max_pages_per_seq, split ? st->ws : st->qkv32,
+      HIP_TRY(launch_rope_kv(sc.qkv, st->Nqkv_pad, M, c.n_q_heads, kv, st->rope_table, st->max_pos, ctx_lens,
+                             cu_seqlens, n_seqs, block_tables, c.max_pages_per_seq, split ? sc.ws : sc.qkv32,
                              qkv_splits, split ? g.bias : nullptr, s));
       g.bias = nullptr;
     }
     {  // a4: attention
-      Timer t(st, s, T_ATTN);
+      Timer t(st, s, timed, T_ATTN);
       if (ctx_lens)
-        HIP_TRY(launch_attn_decode(st->qkv, st->Nqkv_pad, M, c.n_q_heads, kv, ctx_lens, st->attn_items,
-                                   st->attn_item_pages, st->part_o, st->part_ml, st->max_chunks, span_len, st->attn,
+        HIP_TRY(launch_attn_decode(sc.qkv, st->Nqkv_pad, M, c.n_q_heads, kv, ctx_lens, sc.attn_items,
+                                   sc.attn_item_pages, sc.part_o, sc.part_ml, st->max_chunks, span_len, sc.attn,
                                    layout_paired(st->dq), s));
       else
-        HIP_TRY(launch_attn_prefill(st->qkv, st->Nqkv_pad, M, n_seqs, c.n_q_heads, kv, cu_seqlens, block_tables,
-                                    c.max_pages_per_seq, st->attn, layout_paired(st->dq), s));
+        HIP_TRY(launch_attn_prefill(sc.qkv, st->Nqkv_pad, M, n_seqs, c.n_q_heads, kv, cu_seqlens, block_tables,
+                                    c.max_pages_per_seq, sc.attn, layout_paired(st->dq), s));
     }
     {  // a5: output projection + residual -> h (fp32)
-      Timer t(st, s, T_O);
-      g.A = st->attn; g.a_layout = layout_paired(st->dq);
+      Timer t(st, s, timed, T_O);
+      g.A = sc.attn; g.a_layout = layout_paired(st->dq);
       g.W = st->wo + (int64_t)l * st->d_pad * st->dq; g.Kpad = st->dq; g.Npad = st->d_pad;
-      g.N_store = (int)d; g.out = st->h; g.ldo = d; g.out_f32 = 1;
+      g.N_store = (int)d; g.out = sc.h; g.ldo = d; g.out_f32 = 1;
       g.residual = x; g.ldr = d; g.residual_f32 = x_f32; g.epilogue = EPI_RESIDUAL;
       g.splits_used = fuse_reduce ? &o_splits : nullptr;
       HIP_TRY(launch_gemm(g, s));
       g.splits_used = nullptr;
     }
     {  // a6: pre-MLP RMSNorm (forms h = x + partials first if the projection was split)
-      Timer t(st, s, T_NORM);
+      Timer t(st, s, timed, T_NORM);
       if (o_splits > 1)
-        HIP_TRY(launch_rmsnorm_sum(x, x_f32, d, st->ws, o_splits, st->d_pad, st->h, d, st->g_mlp + (int64_t)l * d,
-                                   c.rms_eps, M, (int)d, st->y, layout_paired(d), s));
+        HIP_TRY(launch_rmsnorm_sum(x, x_f32, d, sc.ws, o_splits, st->d_pad, sc.h, d, st->g_mlp + (int64_t)l * d,
+                                   c.rms_eps, M, (int)d, sc.y, layout_paired(d), s));
       else
-        HIP_TRY(launch_rmsnorm(st->h, 1, d, st->g_mlp + (int64_t)l * d, c.rms_eps, M, (int)d, st->y, layout_paired(d), s));
+        HIP_TRY(launch_rmsnorm(sc.h, 1, d, st->g_mlp + (int64_t)l * d, c.rms_eps, M, (int)d, sc.y, layout_paired(d), s));
     }
     {  // a7: gate/up projection + SwiGLU
-      Timer t(st, s, T_GU);
-      g.A = st->y; g.a_layout = layout_paired(d);
+      Timer t(st, s, timed, T_GU);
+      g.A = sc.y; g.a_layout = layout_paired(d);
       g.W = st->wgu + (int64_t)l * st->Ngu_pad * d; g.Kpad = d; g.Npad = st->Ngu_pad;
-      g.N_store = (int)st->Fpad; g.out = st->u; g.ldo = st->Fpad; g.u_layout = layout_paired(st->Fpad); g.out_f32 = 0;
+      g.N_store = (int)st->Fpad; g.out = sc.u; g.ldo = st->Fpad; g.u_layout = layout_paired(st->Fpad); g.out_f32 = 0;
       g.residual = nullptr; g.ldr = 0; g.residual_f32 = 0; g.epilogue = EPI_SWIGLU;
       HIP_TRY(launch_gemm(g, s));
     }
     {  // a8: down projection + residual -> next layer's stream (fp32), or the stage output (bf16)
-      Timer t(st, s, T_DOWN);
-      g.A = st->u; g.a_layout = layout_paired(st->Fpad);
+      Timer t(st, s, timed, T_DOWN);
+      g.A = sc.u; g.a_layout = layout_paired(st->Fpad);
       g.W = st->wd + (int64_t)l * st->d_pad * st->Fpad; g.Kpad = st->Fpad; g.Npad = st->d_pad;
       g.N_store = (int)d; g.out = x_next; g.ldo = d; g.out_f32 = last ? 0 : 1;
-      g.residual = st->h; g.ldr = d; g.residual_f32 = 1; g.epilogue = EPI_RESIDUAL;
+      g.residual = sc.h; g.ldr = d; g.residual_f32 = 1; g.epilogue = EPI_RESIDUAL;
       down_splits = 1;
       g.splits_used = last || !fuse_reduce ? nullptr : &down_splits;  // the stage output has no norm behind it
       HIP_TRY(launch_gemm(g, s));
@@ -270,7 +281,7 @@ int run_layers(tdp_stage* st, const void* hidden_in, void* hidden_out, int M, co
 
 extern "C" {
 
-int tdp_abi_version(void) { return 3; }
+int tdp_abi_version(void) { return 4; }
 
 const char* tdp_last_error(void) { return g_err.c_str(); }
 
@@ -312,30 +323,41 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
   A(&st->bqkv, L * st->Nqkv_pad, true);
   A(&st->kpool, L * st->pool_bytes, true);
   A(&st->vpool, L * st->pool_bytes, true);
-  const int64_t M = (st->maxM + 1) & ~1;  // row pairs: pair-interleaved activation buffers
-  A(&st->y, M * d, true);
-  A(&st->qkv, M * st->Nqkv_pad, true);
-  A(&st->qkv32, M * st->Nqkv_pad, true);
-  A(&st->attn, M * st->dq, true);
-  A(&st->h, M * d, true);
-  A(&st->u, M * st->Fpad, true);
-  A(&st->xa, M * d, true);
-  A(&st->xb, M * d, true);
-  {
-    int64_t maxN = st->Ngu_pad > st->Nqkv_pad ? st->Ngu_pad : st->Nqkv_pad;
-    if (st->d_pad > maxN) maxN = st->d_pad;
-    const int64_t mdec = M < 512 ? M : 512;
-    st->ws_elems = 8 * mdec * maxN;
-    if (st->ws_elems > (64ll << 20)) st->ws_elems = 64ll << 20;
-    A(&st->ws, st->ws_elems, false);
+  st->n_scratch = c.decode_micro_batches == 2 ? 2 : 1;
+  // the second set only ever holds half a decode batch
+  for (int i = 0; i < st->n_scratch; ++i) {
+    tdp_stage::Scratch& sc = st->sc[i];
+    const int64_t rows = i == 0 ? st->maxM : (c.max_batch + 1) / 2;
+    const int64_t M = (rows + 1) & ~1;  // row pairs: pair-interleaved activation buffers
+    const int64_t mb = i == 0 ? c.max_batch : (c.max_batch + 1) / 2;
+    A(&sc.y, M * d, true);
+    A(&sc.qkv, M * st->Nqkv_pad, true);
+    A(&sc.qkv32, M * st->Nqkv_pad, true);
+    A(&sc.attn, M * st->dq, true);
+    A(&sc.h, M * d, true);
+    A(&sc.u, M * st->Fpad, true);
+    A(&sc.xa, M * d, true);
+    A(&sc.xb, M * d, true);
+    {
+      int64_t maxN = st->Ngu_pad > st->Nqkv_pad ? st->Ngu_pad : st->Nqkv_pad;
+      if (st->d_pad > maxN) maxN = st->d_pad;
+      const int64_t mdec = st->maxM + 1 < 512 ? ((st->maxM + 1) & ~1) : 512;
+      st->ws_elems = 8 * mdec * maxN;
+      if (st->ws_elems > (64ll << 20)) st->ws_elems = 64ll << 20;
+      A(&sc.ws, st->ws_elems, false);
+    }
+    A(&sc.part_o, mb * c.n_q_heads * st->max_chunks * dh, false);
+    A(&sc.part_ml, mb * c.n_q_heads * st->max_chunks * 2, false);
+    A(&sc.attn_items, mb * st->max_chunks, false);
+    // spans longer than the minimum round the span count up: up to (1024 / 256 - 1) extra minimum spans' worth
+    A(&sc.attn_item_pages, mb * (st->max_chunks + kDecodeSpanMax / kDecodeSpanMin) * (kDecodeSpanMin / 16), false);
+    A(&sc.attn_n_items, 1, true);
   }
-  A(&st->part_o, (int64_t)c.max_batch * c.n_q_heads * st->max_chunks * dh, false);
-  A(&st->part_ml, (int64_t)c.max_batch * c.n_q_heads * st->max_chunks * 2, false);
-  A(&st->attn_items, (int64_t)c.max_batch * st->max_chunks, false);
-  // spans longer than the minimum round the span count up: up to (1024 / 256 - 1) extra minimum spans' worth
-  A(&st->attn_item_pages, (int64_t)c.max_batch * (st->max_chunks + kDecodeSpanMax / kDecodeSpanMin) * (kDecodeSpanMin / 16),
-    false);
-  A(&st->attn_n_items, 1, true);
+  if (e == hipSuccess && st->n_scratch == 2) {
+    e = hipStreamCreateWithFlags(&st->aux_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&st->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&st->ev_join, hipEventDisableTiming);
+  }
   A(&st->rope_table, (int64_t)st->max_pos * (dh / 2), false);
   A(&st->check_owner, c.num_pages, false);
   A(&st->check_res, 2, true);
@@ -363,12 +385,19 @@ int tdp_stage_create(const tdp_stage_config* cfg, tdp_stage** out) {
 void tdp_stage_destroy(tdp_stage* st) {
   if (!st) return;
   (void)hipDeviceSynchronize();
-  void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->bqkv, st->kpool, st->vpool, st->y,
-                  st->qkv, st->qkv32, st->attn, st->h, st->u, st->xa, st->xb, st->ws, st->part_o, st->part_ml,
-                  st->attn_items, st->attn_n_items, st->attn_item_pages, st->rope_table, st->check_owner,
-                  st->check_res};
+  void* ptrs[] = {st->wqkv, st->wo, st->wgu, st->wd, st->g_attn, st->g_mlp, st->bqkv, st->kpool, st->vpool,
+                  st->rope_table, st->check_owner, st->check_res};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
+  for (tdp_stage::Scratch& sc : st->sc) {
+    void* sp[] = {sc.y, sc.qkv, sc.qkv32, sc.attn, sc.h, sc.u, sc.xa, sc.xb, sc.ws, sc.part_o, sc.part_ml, sc.attn_items,
+                  sc.attn_n_items, sc.attn_item_pages};
+    for (void* p : sp)
+      if (p) (void)hipFree(p);
+  }
+  if (st->ev_fork) (void)hipEventDestroy(st->ev_fork);
+  if (st->ev_join) (void)hipEventDestroy(st->ev_join);
+  if (st->aux_stream) (void)hipStreamDestroy(st->aux_stream);
   for (hipEvent_t ev : st->ev_start) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : st->ev_stop) (void)hipEventDestroy(ev);
   delete st;
@@ -494,7 +523,7 @@ int tdp_stage_prefill(tdp_stage* st, const void* hidden_in, const int32_t* cu_se
   if (total_tokens > st->cfg.max_tokens) return fail(TDP_EINVAL, "total_tokens exceeds max_tokens");
   if (n_seqs == 0 || total_tokens == 0) return TDP_OK;
   if (!hidden_in || !hidden_out || !cu_seqlens || !block_tables) return fail(TDP_EINVAL, "null pointer");
-  return run_layers(st, hidden_in, hidden_out, total_tokens, nullptr, cu_seqlens, n_seqs, block_tables,
+  return run_layers(st, st->sc[0], true, hidden_in, hidden_out, total_tokens, nullptr, cu_seqlens, n_seqs, block_tables,
                     (hipStream_t)stream);
 }
 
@@ -505,8 +534,26 @@ int tdp_stage_decode(tdp_stage* st, const void* hidden_in, const int32_t* ctx_le
   if (batch > st->cfg.max_batch) return fail(TDP_EINVAL, "batch exceeds max_batch");
   if (batch == 0) return TDP_OK;
   if (!hidden_in || !hidden_out || !ctx_lens || !block_tables) return fail(TDP_EINVAL, "null pointer");
-  return run_layers(st, hidden_in, hidden_out, batch, ctx_lens, nullptr, batch, block_tables,
-                    (hipStream_t)stream);
+  hipStream_t s = (hipStream_t)stream;
+  if (st->n_scratch < 2 || batch < 2)
+    return run_layers(st, st->sc[0], true, hidden_in, hidden_out, batch, ctx_lens, nullptr, batch, block_tables, s);
+  // Two half-batches, one on the caller's stream and one on the stage's second stream, so that one half's
+  // attention (bound by reading the cache, Sec. 2.1) can run beside the other half's projections.  The
+  // second stream starts after everything already queued on the caller's stream and is joined at the end.
+  const int half = (batch + 1) / 2;
+  const int64_t d = st->cfg.d_model;
+  st->ev_used = 0;  // per-class timing is not recorded for the two-stream form
+  HIP_TRY(hipEventRecord(st->ev_fork, s));
+  HIP_TRY(hipStreamWaitEvent(st->aux_stream, st->ev_fork, 0));
+  int rc = run_layers(st, st->sc[0], false, hidden_in, hidden_out, half, ctx_lens, nullptr, half, block_tables, s);
+  if (rc != TDP_OK) return rc;
+  rc = run_layers(st, st->sc[1], false, (const uint16_t*)hidden_in + (int64_t)half * d,
+                  (uint16_t*)hidden_out + (int64_t)half * d, batch - half, ctx_lens + half, nullptr, batch - half,
+                  block_tables + (int64_t)half * st->cfg.max_pages_per_seq, st->aux_stream);
+  if (rc != TDP_OK) return rc;
+  HIP_TRY(hipEventRecord(st->ev_join, st->aux_stream));
+  HIP_TRY(hipStreamWaitEvent(s, st->ev_join, 0));
+  return TDP_OK;
 }
 
 static int check_tables(tdp_stage* st, int decode, const int32_t* lens, const int32_t* block_tables, int n_rows,

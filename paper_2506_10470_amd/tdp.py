@@ -27,7 +27,8 @@ class StageConfig(C.Structure):
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("page_size", C.c_int32),
                 ("num_pages", C.c_int32), ("max_batch", C.c_int32), ("max_tokens", C.c_int32),
                 ("max_seqs", C.c_int32), ("max_pages_per_seq", C.c_int32),
-                ("kv_dtype", C.c_int32), ("k_scale", C.c_float), ("v_scale", C.c_float)]
+                ("kv_dtype", C.c_int32), ("k_scale", C.c_float), ("v_scale", C.c_float),
+                ("decode_micro_batches", C.c_int32)]
 
 
 class EndsConfig(C.Structure):

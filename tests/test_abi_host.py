@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     for name in declared:
         assert hasattr(tdp.lib, name), name
         assert name in tdp._SIGS, "binding lacks " + name
-    assert tdp.tdp_abi_version() == 3
+    assert tdp.tdp_abi_version() == 4
 
 
 @pytest.mark.parametrize("bad", [
@@ -34,6 +34,7 @@ def test_every_declared_symbol_is_exported():
     dict(max_batch=0, max_tokens=0), dict(max_batch=-1), dict(max_pages_per_seq=0), dict(rope_base=0.0),
     dict(max_tokens=8, max_seqs=0), dict(kv_dtype=2), dict(kv_dtype=-1),
     dict(kv_dtype=1, k_scale=-1.0), dict(kv_dtype=1, v_scale=float("inf")), dict(kv_dtype=1, k_scale=float("nan")),
+    dict(decode_micro_batches=3), dict(decode_micro_batches=-1),
 ])
 def test_create_rejects_bad_config_before_any_gpu_work(bad):
     with pytest.raises(tdp.TdpError) as e:

@@ -82,14 +82,15 @@ def written_slot_mask(st: Stage, tables: np.ndarray, first: np.ndarray, last: np
     return mk, mv
 
 
-def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_pages_per_seq=None, span=0):
+def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_pages_per_seq=None, span=0,
+                    micro_batches=0):
     sh = W.SHAPES[shape_name]
     if n_layers:
         sh = sh.with_layers(n_layers)
     ctx_lens = np.asarray(ctx_lens, dtype=np.int64)
     B = len(ctx_lens)
     batch = W.make_decode_batch(ctx_lens, max_pages_per_seq=max_pages_per_seq)
-    with Stage(tdp, sh, batch.num_pages, B, 0, 0, batch.tables.shape[1]) as st:
+    with Stage(tdp, sh, batch.num_pages, B, 0, 0, batch.tables.shape[1], decode_micro_batches=micro_batches) as st:
         st.poison()
         tdp.tdp_stage_set_decode_span(st.h, span)
         caches = import_kv(tdp, st, ctx_lens, batch.tables, stream_id)
@@ -259,6 +260,55 @@ def test_model_dimension_above_8192(tdp):
     registers; decode at a batch that splits K (partials summed by the consumers) and a prefill."""
     run_decode_case(tdp, "tiny_wide", [3, 40, 17, 0, 100, 64, 31, 5])
     run_prefill_case(tdp, "tiny_wide", [20, 1, 33], decode_steps=1)
+
+
+@pytest.mark.parametrize("shape,ctx,n_layers", [
+    ("tiny_gqa", [0, 1, 15, 16, 31, 255, 256, 257, 700, 40, 3], None),     # odd batch: halves of 6 and 5
+    ("tiny", [20, 33], None),                                              # one request per half
+    ("tiny_h128", [64], None),                                             # a batch of one takes the plain path
+    ("7b_quarter", None, 2),                                               # batch 200: split-K partials in both halves
+])
+def test_decode_as_two_half_batches_on_two_streams(tdp, shape, ctx, n_layers):
+    """decode_micro_batches = 2: the batch runs as two halves, the second on the stage's own second
+    stream with its own scratch buffers, forked from and joined to the caller's stream.  Outputs, the
+    appended K/V and every untouched slot are held to the same bounds as the one-batch form."""
+    if ctx is None:
+        ctx = np.minimum(W.decode_ctx_lens(shape, 200), 300)
+    run_decode_case(tdp, shape, ctx, n_layers=n_layers, micro_batches=2)
+
+
+def test_two_half_batches_follow_the_callers_stream(tdp):
+    """The forked second stream must wait for work queued earlier on the caller's stream (here: the copy that
+    produces the input) and the caller's stream must wait for it (here: the copy of the output), on a
+    stream that is not the default one; repeated, so that a later step may not overtake an earlier one."""
+    sh = W.SHAPES["tiny_gqa"]
+    ctx = np.array([5, 40, 300, 77, 16, 255, 31], dtype=np.int64)
+    batch = W.make_decode_batch(ctx)
+    B = len(ctx)
+    outs = {}
+    for micro in (0, 2):
+        with Stage(tdp, sh, batch.num_pages, B, 0, 0, batch.tables.shape[1], decode_micro_batches=micro) as st:
+            import_kv(tdp, st, ctx, batch.tables, 9)
+            src = W.hidden_states(sh, B, 9, device="cuda")
+            ctx_d, tab_d = i32(ctx), i32(batch.tables)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            got = []
+            with torch.cuda.stream(side):
+                for rep in range(4):
+                    x = torch.zeros_like(src)
+                    out = torch.zeros_like(src)
+                    x.copy_(src, non_blocking=True)                       # queued on `side`, just before the call
+                    tdp.tdp_stage_decode(st.h, x, ctx_d, tab_d, B, out, side)
+                    got.append(out.clone())                               # queued on `side`, right behind it
+            side.synchronize()
+            outs[micro] = [g.view(torch.int16).cpu() for g in got]
+    for rep in range(4):
+        assert torch.equal(outs[2][rep], outs[2][0])
+        # the halves take other tile shapes than the whole batch, so the two forms agree within rounding
+        a = outs[2][rep].view(torch.bfloat16).double().numpy()
+        b = outs[0][rep].view(torch.bfloat16).double().numpy()
+        assert row_rel_err(a, b) <= 1e-2
 
 
 def test_decode_is_invariant_under_block_table_permutation(tdp):
