@@ -100,10 +100,45 @@ hipError_t launch_rmsnorm(const void* x, int x_is_f32, int64_t ldx, const float*
   return hipGetLastError();
 }
 
+// Sum of split-K partials, eight consecutive columns at a time: acc = p_0 + p_1 + ... in split order
+// (partial z of a row lies z * split_stride floats further on).  The partials are fetched UN
+// splits at a time so that all of a thread's loads are in flight together: a loop that loads and adds
+// one split per turn pays one memory round trip per split, which is what a launch of few rows
+// (small decode batches) consists of.  `splits` is uniform, so the guards are scalar branches.
+template <int NCOL, int UN>
+__device__ __forceinline__ void sum_partials8(const float* const (&first)[NCOL], int64_t split_stride, int splits,
+                                              float (&acc)[NCOL][8]) {
+#pragma unroll
+  for (int c = 0; c < NCOL; ++c)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[c][i] = 0.f;
+  for (int z0 = 0; z0 < splits; z0 += UN) {
+    float f[UN][NCOL][8];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      if (z0 + u < splits) {
+#pragma unroll
+        for (int c = 0; c < NCOL; ++c) load8<true>(first[c] + (int64_t)(z0 + u) * split_stride, 0, f[u][c]);
+      } else {
+#pragma unroll
+        for (int c = 0; c < NCOL; ++c)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) f[u][c][i] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u)
+#pragma unroll
+      for (int c = 0; c < NCOL; ++c)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[c][i] += f[u][c][i];
+  }
+}
+
 // The row is formed first: h = residual + the split-K partials of the projection in front of the
-// norm (summed in split order), stored as the fp32 residual stream, then normalised.  A thread
-// re-reads only what it wrote itself.  1024 threads per row: at d = 8192 every thread has one
-// 8-element chunk and all of its loads are in flight at once.
+// norm (summed in split order), stored as the fp32 residual stream, then normalised.  1024 threads
+// per row: at d = 8192 every thread has one 8-element chunk, which it keeps in registers between the
+// two passes; beyond that a thread re-reads what it wrote itself.
 template <bool F32_RES>
 __global__ __launch_bounds__(1024) void rmsnorm_sum_kernel(const void* __restrict__ residual, int64_t ldr,
                                                           const float* __restrict__ ws, int splits, int M,
@@ -115,22 +150,25 @@ __global__ __launch_bounds__(1024) void rmsnorm_sum_kernel(const void* __restric
                            : (const void*)((const bf16*)residual + (int64_t)row * ldr);
   float* hr = h_out + (int64_t)row * ldh;
   const int chunks = d / 8;
+  const int64_t split_stride = (int64_t)M * ld_ws;
   float ss = 0.f;
+  float keep[8];  // this thread's first chunk of h
   for (int c = threadIdx.x; c < chunks; c += 1024) {
-    float f[8], acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int z = 0; z < splits; ++z) {
-      load8<true>(ws + ((int64_t)z * M + row) * ld_ws, c, f);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] += f[i];
-    }
+    float f[8], acc[1][8];
     load8<F32_RES>(rr, c, f);
+    const float* const first[1] = {ws + (int64_t)row * ld_ws + c * 8};
+    sum_partials8<1, 8>(first, split_stride, splits, acc);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      acc[i] += f[i];
-      ss += acc[i] * acc[i];
+      acc[0][i] += f[i];
+      ss += acc[0][i] * acc[0][i];
     }
-    *reinterpret_cast<f32x4*>(hr + c * 8) = f32x4{acc[0], acc[1], acc[2], acc[3]};
-    *reinterpret_cast<f32x4*>(hr + c * 8 + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
+    *reinterpret_cast<f32x4*>(hr + c * 8) = f32x4{acc[0][0], acc[0][1], acc[0][2], acc[0][3]};
+    *reinterpret_cast<f32x4*>(hr + c * 8 + 4) = f32x4{acc[0][4], acc[0][5], acc[0][6], acc[0][7]};
+    if (c == (int)threadIdx.x) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) keep[i] = acc[0][i];
+    }
   }
   __shared__ float red[16];
   ss = wave_sum(ss);
@@ -142,7 +180,12 @@ __global__ __launch_bounds__(1024) void rmsnorm_sum_kernel(const void* __restric
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
   for (int c = threadIdx.x; c < chunks; c += 1024) {
     float f[8];
-    load8<true>(hr, c, f);
+    if (c == (int)threadIdx.x) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) f[i] = keep[i];
+    } else {
+      load8<true>(hr, c, f);
+    }
     const f32x4 g0 = *reinterpret_cast<const f32x4*>(gain + c * 8);
     const f32x4 g1 = *reinterpret_cast<const f32x4*>(gain + c * 8 + 4);
     bf16x8 o;
@@ -204,20 +247,24 @@ __global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv
                                                       int splits, int n_tokens, const float* __restrict__ bias,
                                                       int v_to_row) {
   const int t = blockIdx.x;
-  // eight consecutive projection outputs of this token, starting at column col
-  auto proj8 = [&](int col, float (&f)[8]) {
-    load8<true>(proj + (int64_t)t * ld + col, 0, f);
-    for (int z = 1; z < splits; ++z) {
-      float g[8];
-      load8<true>(proj + ((int64_t)z * n_tokens + t) * ld + col, 0, g);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) f[i] += g[i];
-    }
+  // NCOL groups of eight consecutive projection outputs of this token, starting at columns col[]
+  const int64_t split_stride = (int64_t)n_tokens * ld;
+  auto proj8 = [&](auto& f, auto... col) {
+    constexpr int NCOL = sizeof...(col);
+    const float* const first[NCOL] = {(proj + (int64_t)t * ld + col)...};
+    const int cols[NCOL] = {col...};
+    // one split per turn: fetching several at once costs registers, hence resident waves, and at the
+    // batch sizes where this kernel takes measurable time (hundreds of rows) that loses more than it
+    // gains (measured at batch 512: 23 us per launch against 21)
+    sum_partials8<NCOL, 1>(first, split_stride, splits, f);
     if (bias) {
-      float g[8];
-      load8<true>(bias + col, 0, g);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) f[i] += g[i];
+      for (int c = 0; c < NCOL; ++c) {
+        float g[8];
+        load8<true>(bias + cols[c], 0, g);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[c][i] += g[i];
+      }
     }
   };
   int seq, pos;
@@ -235,9 +282,10 @@ __global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv
     const int head = w / per_head;
     const int c0 = (w % per_head) * 8;
     bf16* hp = row + (int64_t)head * dh;
-    float a[8], b[8];
-    proj8(head * dh + c0, a);
-    proj8(head * dh + half + c0, b);
+    float ab[2][8];
+    proj8(ab, head * dh + c0, head * dh + half + c0);
+    const float(&a)[8] = ab[0];
+    const float(&b)[8] = ab[1];
     float fra[8], frb[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -278,8 +326,9 @@ __global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv
   }
   const int v_col = (n_q_heads + kv.n_kv_heads) * dh;
   for (int w8 = threadIdx.x; w8 < kv.n_kv_heads * dh / 8; w8 += THREADS) {
-    float f[8];
-    proj8(v_col + w8 * 8, f);
+    float fv[1][8];
+    proj8(fv, v_col + w8 * 8);
+    const float(&f)[8] = fv[0];
     if (v_to_row) {  // prefill: the values are appended page by page (v_append_pages_kernel)
       bf16x8 o;
 #pragma unroll

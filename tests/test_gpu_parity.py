@@ -84,7 +84,7 @@ def written_slot_mask(st: Stage, tables: np.ndarray, first: np.ndarray, last: np
 
 def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_pages_per_seq=None, span=0,
                     micro_batches=0):
-    sh = W.SHAPES[shape_name]
+    sh = shape_name if isinstance(shape_name, W.StageShape) else W.SHAPES[shape_name]
     if n_layers:
         sh = sh.with_layers(n_layers)
     ctx_lens = np.asarray(ctx_lens, dtype=np.int64)
@@ -122,7 +122,7 @@ def run_decode_case(tdp, shape_name, ctx_lens, n_layers=None, stream_id=1, max_p
 
 
 def run_prefill_case(tdp, shape_name, seq_lens, n_layers=None, stream_id=2, decode_steps=0):
-    sh = W.SHAPES[shape_name]
+    sh = shape_name if isinstance(shape_name, W.StageShape) else W.SHAPES[shape_name]
     if n_layers:
         sh = sh.with_layers(n_layers)
     seq_lens = np.asarray(seq_lens, dtype=np.int64)
