@@ -180,6 +180,7 @@ def run_prefill_case(tdp, shape_name, seq_lens, n_layers=None, stream_id=2, deco
     (512, 1280, 2048, 0, 0, 0), (1000, 256, 64, 0, 0, 1), (257, 516, 192, 0, 2, 1),
     # every kernel variant (1: 256 x 256 tile, 2: 128 x 256, 3: 128 x 128), ragged M and N, split-K
     (300, 768, 1024, 1, 1, 0), (257, 516, 192, 1, 2, 1), (513, 520, 448, 1, 2, 1),
+    (300, 516, 256, 1, 1, 1), (513, 260, 128, 1, 1, 1),   # whole-tile residual epilogue, ragged M and N
     (100, 384, 256, 2, 3, 0), (130, 1024, 320, 2, 1, 1), (70, 260, 128, 2, 1, 0), (65, 512, 256, 2, 2, 1),
     (100, 384, 256, 3, 2, 0), (300, 640, 1024, 3, 1, 1), (7, 256, 512, 3, 4, 1),
 ])
