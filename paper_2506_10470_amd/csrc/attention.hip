@@ -25,6 +25,9 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf: exp2 gives exa
 // finished there (no partials in HBM), longer ones leave one partial per span for the merge
 // kernel.  The item list is compact (built once per decode step by attn_plan_kernel), so the grid
 // holds no workgroup that finds nothing to do except at its very end.
+// Keys and values are requested as non-temporal: a launch reads each of them exactly once, and as
+// ordinary loads they evict everything else from L2 on their way through (measured: 5.9 TB/s against
+// 5.5 at batch 512, 5.7 against 5.2 at batch 256).
 // =====================================================================================
 
 // items[i] = (request, span index, tokens to attend to = ctx + 1, 0) for i < n_items[0], and
@@ -208,14 +211,14 @@ __global__ __launch_bounds__(256, 3) void attn_decode_kernel(const bf16* __restr
         for (int t = 0; t < NT; ++t)
 #pragma unroll
           for (int l = 0; l < KS / 2; ++l)
-            blk.kf[t >> 1][(t & 1) * (KS / 2) + l] = *reinterpret_cast<const bf16x8*>(kp + (t * 4) * DH + l * 64);
+            blk.kf[t >> 1][(t & 1) * (KS / 2) + l] = ld_bf16x8_nt(reinterpret_cast<const bf16*>(kp + (t * 4) * DH + l * 64));
       } else {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           const int tok = krow0 + t * 4;
           const bf16* kp = kpool + ((page[tok >> 4 & 1] * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
 #pragma unroll
-          for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8(kp + kk * 32);
+          for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8_nt(kp + kk * 32);
         }
       }
     };
@@ -229,12 +232,12 @@ __global__ __launch_bounds__(256, 3) void attn_decode_kernel(const bf16* __restr
         const int64_t vpage = kg == 0 ? page[0] : kg == 1 ? page[1] : kg == 2 ? page[2] : page[3];
         const uint8_t* vp = vpool8 + ((vpage * Hkv + kvh) * DH + r16) * 16;
 #pragma unroll
-        for (int d = 0; d < DT; ++d) blk.vf[d] = *reinterpret_cast<const bf16x8*>(vp + d * 16 * 16);
+        for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8_nt(reinterpret_cast<const bf16*>(vp + d * 16 * 16));
       } else {
         const int64_t vpage = kg < 2 ? page[0] : page[1];
         const bf16* vp = vpool + ((vpage * Hkv + kvh) * DH + r16) * 16 + (kg & 1) * 8;
 #pragma unroll
-        for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8(vp + d * 16 * 16);
+        for (int d = 0; d < DT; ++d) blk.vf[d] = ld_bf16x8_nt(vp + d * 16 * 16);
       }
     };
     auto compute_block = [&](int tb, KBlock& blk, VBlock& vblk) {

@@ -29,6 +29,13 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 __device__ __forceinline__ bf16x8 ld_bf16x8(const bf16* p) {
   return *reinterpret_cast<const bf16x8*>(p);
 }
+// The same load marked non-temporal: for data a launch reads exactly once (a request's keys and values in
+// decode), so that it does not displace what other workgroups share in L2.
+__device__ __forceinline__ bf16x8 ld_bf16x8_nt(const bf16* p) {
+  typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4_t;
+  const u32x4_t raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return __builtin_bit_cast(bf16x8, raw);
+}
 __device__ __forceinline__ void st_bf16x8(bf16* p, bf16x8 v) {
   *reinterpret_cast<bf16x8*>(p) = v;
 }
