@@ -134,7 +134,7 @@ __device__ __forceinline__ void gemm_epilogue16_residual(const GemmParams& p, f3
       for (int wt = 0; wt < WT; ++wt) {
         const int n = min(col0 + wt * 16 + kq * 4, n_last);
         if (p.res_f32) {
-          r[ab][wt] = *reinterpret_cast<const f32x4*>((const float*)p.residual + (int64_t)m * p.ldr + n);
+          r[ab][wt] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>((const float*)p.residual + (int64_t)m * p.ldr + n));
         } else {
           const bf16x4 t = *reinterpret_cast<const bf16x4*>((const bf16*)p.residual + (int64_t)m * p.ldr + n);
           r[ab][wt] = f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
