@@ -524,6 +524,15 @@ def test_decode_every_span_length(tdp, span):
             tdp.tdp_stage_set_decode_span(st.h, 300)
 
 
+@pytest.mark.parametrize("span", [0, 256, 4096])
+def test_decode_contexts_far_beyond_the_benchmark(tdp, span):
+    """Contexts of up to 20,000 tokens (the benchmark stops at 4096): dozens of spans per request
+    (79 at the shortest span length), page lists of over a thousand entries, and a batch that mixes
+    them with a one-token context."""
+    ctx = [20000, 0, 9000, 16383, 16384, 4097, 12345]
+    run_decode_case(tdp, "tiny_gqa", ctx, n_layers=1, max_pages_per_seq=20000 // 16 + 2, span=span)
+
+
 def test_decode_step_replays_from_a_hip_graph(tdp):
     """A serving loop would capture the decode step once and replay it: the call only enqueues
     kernels on the stream it is given (no allocation, no synchronisation, no memset node), so it
