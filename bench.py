@@ -160,7 +160,7 @@ def measured_traffic(workload):
     per = t["per_launch"]
     tot = lambda *ks: sum(per[k]["fetch_bytes"] + per[k]["write_bytes"] for k in ks if k in per)
     src = "stored, not measured in this run: profiles/%s (%s; recorded %s)" % (name, t.get("source", "?"), t.get("recorded", "?"))
-    return {"attention": tot("attn_decode_kernel", "attn_decode_merge_kernel"), "gemm_qkv": tot("gemm_qkv"),
+    return {"attention": tot("attn_decode_kernel"), "gemm_qkv": tot("gemm_qkv"),
             "gemm_o": tot("gemm_o"), "gemm_gate_up": tot("gemm_gate_up"), "gemm_down": tot("gemm_down")}, src
 
 

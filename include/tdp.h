@@ -289,10 +289,12 @@ TDP_API int tdp_probe_mfma_bf16(int32_t iters, int32_t launches, int32_t random_
  * Timing hooks: when enabled, prefill/decode record HIP events around each kernel class on the
  * call's stream; tdp_stage_timing_read synchronises and returns the summed milliseconds of the
  * most recent call per class (order: rmsnorm, gemm_qkv, rope_kv, attention, gemm_o, gemm_gate_up,
- * gemm_down) into ms[7].
+ * gemm_down, attention_merge) into ms[8].  "attention" is the attention kernel alone (prefill or
+ * decode), "attention_merge" the kernel that combines the partial results of decode requests longer
+ * than one span (0 in prefill, and when no request of the batch can be that long).
  */
 TDP_API int tdp_stage_timing_enable(tdp_stage* st, int32_t on);
-TDP_API int tdp_stage_timing_read(tdp_stage* st, float* ms /* host [7] */);
+TDP_API int tdp_stage_timing_read(tdp_stage* st, float* ms /* host [8] */);
 
 /* ---- the two ends of the pipeline ---------------------------------------------------------------
  * What runs in front of the first stage and behind the last one so that a chain of stages turns

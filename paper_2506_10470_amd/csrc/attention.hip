@@ -429,33 +429,41 @@ hipError_t launch_attn_plan(const int32_t* ctx_lens, const int32_t* block_tables
 }
 
 hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
-                              const int32_t* ctx_lens, const int4* items, const int32_t* item_pages, float* part_o,
-                              float* part_ml, int max_spans, int span_len, void* out, OperandLayout out_layout,
-                              hipStream_t s) {
+                              const int4* items, const int32_t* item_pages, float* part_o, float* part_ml,
+                              int max_spans, int span_len, void* out, OperandLayout out_layout, hipStream_t s) {
   if (batch <= 0) return hipSuccess;
   // 8-bit pools hold value / scale: the key scale joins the softmax scale, the value scale the final division
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)kv.head_dim) * (kv.fp8 ? kv.k_scale : 1.0f);
   const float out_scale = kv.fp8 ? kv.v_scale : 1.0f;
   const int max_items = attn_decode_items(batch, max_spans, span_len);
-  const int spans = max_items / batch;
   const unsigned grid = (unsigned)max_items * kv.n_kv_heads;
-  dim3 mgrid(n_q_heads, batch);
 #define TDP_DECODE(DH, KV8)                                                                                        \
   attn_decode_kernel<DH, KV8><<<grid, 256, 0, s>>>((const bf16*)qkv, ld, n_q_heads, kv, items, item_pages, part_o, \
                                                    part_ml, max_spans, span_len, (bf16*)out, out_layout,          \
                                                    scale_log2, out_scale)
   if (kv.head_dim == 128) {
     if (kv.fp8) TDP_DECODE(128, true); else TDP_DECODE(128, false);
-    if (spans > 1)
-      attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
-                                                          span_len, (bf16*)out, out_layout, out_scale);
   } else {
     if (kv.fp8) TDP_DECODE(64, true); else TDP_DECODE(64, false);
-    if (spans > 1)
-      attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans,
-                                                        span_len, (bf16*)out, out_layout, out_scale);
   }
 #undef TDP_DECODE
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_decode_merge(int batch, int n_q_heads, const KvLayout& kv, const int32_t* ctx_lens,
+                                    const float* part_o, const float* part_ml, int max_spans, int span_len, void* out,
+                                    OperandLayout out_layout, hipStream_t s) {
+  if (batch <= 0) return hipSuccess;
+  // with one span per request at most, every request was finished by the attention kernel itself
+  if (attn_decode_items(batch, max_spans, span_len) / batch <= 1) return hipSuccess;
+  const float out_scale = kv.fp8 ? kv.v_scale : 1.0f;
+  dim3 mgrid(n_q_heads, batch);
+  if (kv.head_dim == 128)
+    attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans, span_len,
+                                                        (bf16*)out, out_layout, out_scale);
+  else
+    attn_decode_merge_kernel<64><<<mgrid, 64, 0, s>>>(part_o, part_ml, ctx_lens, n_q_heads, max_spans, span_len,
+                                                      (bf16*)out, out_layout, out_scale);
   return hipGetLastError();
 }
 

@@ -32,7 +32,7 @@ int fail_hip(hipError_t e, const char* what) {
 
 int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 
-enum TimeClass { T_NORM = 0, T_QKV, T_ROPE, T_ATTN, T_O, T_GU, T_DOWN, T_COUNT };
+enum TimeClass { T_NORM = 0, T_QKV, T_ROPE, T_ATTN, T_O, T_GU, T_DOWN, T_MERGE, T_COUNT };
 
 }  // namespace
 
@@ -227,12 +227,16 @@ int run_layers(tdp_stage* st, tdp_stage::Scratch& sc, bool timed, const void* hi
     {  // a4: attention
       Timer t(st, s, timed, T_ATTN);
       if (ctx_lens)
-        HIP_TRY(launch_attn_decode(sc.qkv, st->Nqkv_pad, M, c.n_q_heads, kv, ctx_lens, sc.attn_items,
-                                   sc.attn_item_pages, sc.part_o, sc.part_ml, st->max_chunks, span_len, sc.attn,
-                                   layout_paired(st->dq), s));
+        HIP_TRY(launch_attn_decode(sc.qkv, st->Nqkv_pad, M, c.n_q_heads, kv, sc.attn_items, sc.attn_item_pages,
+                                   sc.part_o, sc.part_ml, st->max_chunks, span_len, sc.attn, layout_paired(st->dq), s));
       else
         HIP_TRY(launch_attn_prefill(sc.qkv, st->Nqkv_pad, M, n_seqs, c.n_q_heads, kv, cu_seqlens, block_tables,
                                     c.max_pages_per_seq, sc.attn, layout_paired(st->dq), s));
+    }
+    if (ctx_lens) {  // a4, second kernel: requests longer than one span are combined from their partials
+      Timer t(st, s, timed, T_MERGE);
+      HIP_TRY(launch_attn_decode_merge(M, c.n_q_heads, kv, ctx_lens, sc.part_o, sc.part_ml, st->max_chunks, span_len,
+                                       sc.attn, layout_paired(st->dq), s));
     }
     {  // a5: output projection + residual -> h (fp32)
       Timer t(st, s, timed, T_O);
@@ -281,7 +285,7 @@ int run_layers(tdp_stage* st, tdp_stage::Scratch& sc, bool timed, const void* hi
 
 extern "C" {
 
-int tdp_abi_version(void) { return 4; }
+int tdp_abi_version(void) { return 5; }
 
 const char* tdp_last_error(void) { return g_err.c_str(); }
 

@@ -137,10 +137,15 @@ int attn_decode_items(int batch, int max_spans, int span_len);
 hipError_t launch_attn_plan(const int32_t* ctx_lens, const int32_t* block_tables, int max_pages_per_seq, int batch,
                             int max_spans, int span_len, int4* items, int32_t* n_items, int32_t* item_pages,
                             hipStream_t s);
+// the attention kernel proper: finishes every request whose context fits one span, leaves fp32 partials
+// (part_o, part_ml) for the others ...
 hipError_t launch_attn_decode(const void* qkv, int64_t ld, int batch, int n_q_heads, const KvLayout& kv,
-                              const int32_t* ctx_lens, const int4* items, const int32_t* item_pages, float* part_o,
-                              float* part_ml, int max_spans, int span_len, void* out, OperandLayout out_layout,
-                              hipStream_t s);
+                              const int4* items, const int32_t* item_pages, float* part_o, float* part_ml,
+                              int max_spans, int span_len, void* out, OperandLayout out_layout, hipStream_t s);
+// ... which this combines (a no-op launch-wise when no request can have more than one span)
+hipError_t launch_attn_decode_merge(int batch, int n_q_heads, const KvLayout& kv, const int32_t* ctx_lens,
+                                    const float* part_o, const float* part_ml, int max_spans, int span_len, void* out,
+                                    OperandLayout out_layout, hipStream_t s);
 // diagnostic: dst[i] = E4M3 code of src[i] / scale (to_codes) or dst[i] = value of code src[i] (fp32), through the
 // same device functions the KV kernels use (the decode direction through the hardware conversion)
 hipError_t launch_e4m3_convert(int to_codes, const void* src, void* dst, int64_t n, float scale, hipStream_t s);

@@ -18,7 +18,8 @@ WEIGHT_IDS = {"wq": WQ, "wk": WK, "wv": WV, "wo": WO, "wg": WG, "wu": WU, "wd": 
 F32, BF16 = 0, 1
 HOST, DEVICE = 0, 1
 KV_BF16, KV_FP8_E4M3 = 0, 1
-TIMING_CLASSES = ("rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gate_up", "gemm_down")
+TIMING_CLASSES = ("rmsnorm", "gemm_qkv", "rope_kv", "attention", "gemm_o", "gemm_gate_up", "gemm_down",
+                  "attention_merge")
 
 
 class StageConfig(C.Structure):

@@ -25,7 +25,7 @@ def test_every_declared_symbol_is_exported():
     for name in declared:
         assert hasattr(tdp.lib, name), name
         assert name in tdp._SIGS, "binding lacks " + name
-    assert tdp.tdp_abi_version() == 4
+    assert tdp.tdp_abi_version() == 5
 
 
 @pytest.mark.parametrize("bad", [
