@@ -282,11 +282,15 @@ def empirical_section(tdp, st, n_layers, stream):
     k, _, n = tdp.tdp_stage_kv_pool(st.h, 0)
     total = n * n_layers                              # the layers' K pools are one contiguous allocation
     out = {}
-    for name, size, scattered in (("hbm_read_in_order_gbs", 2 << 30, False),
-                                  ("hbm_read_4k_scattered_gbs", 2 << 30, True),
-                                  ("hbm_read_in_order_large_gbs", 16 << 30, False),
-                                  ("hbm_read_4k_scattered_large_gbs", 16 << 30, True)):
-        nbytes, ms = tdp.tdp_probe_hbm_read(k, min(size, total), scattered, 5, stream)
+    for name, size, scattered, nt in (("hbm_read_in_order_gbs", 2 << 30, False, False),
+                                      ("hbm_read_4k_scattered_gbs", 2 << 30, True, False),
+                                      ("hbm_read_in_order_large_gbs", 16 << 30, False, False),
+                                      ("hbm_read_4k_scattered_large_gbs", 16 << 30, True, False),
+                                      # the same reads marked non-temporal, as the kernels mark what they read once
+                                      ("hbm_read_in_order_non_temporal_gbs", 2 << 30, False, True),
+                                      ("hbm_read_4k_scattered_non_temporal_gbs", 2 << 30, True, True),
+                                      ("hbm_read_4k_scattered_non_temporal_large_gbs", 16 << 30, True, True)):
+        nbytes, ms = tdp.tdp_probe_hbm_read(k, min(size, total), scattered, 5, stream, non_temporal=nt)
         out[name] = round(nbytes / ms / 1e6, 1)
         out[name.replace("_gbs", "_footprint_bytes")] = nbytes
     flop, ms = tdp.tdp_probe_mfma_bf16(8192, 5, True, stream)
@@ -480,6 +484,8 @@ def main():
     ap.add_argument("--micro-batches", type=int, default=0, choices=[0, 2],
                     help="2: also time the headline step as two half-batches on two streams (decode_micro_batches)")
     ap.add_argument("--no-others", action="store_true", help="skip the lean passes over the other configurations")
+    ap.add_argument("--decode-span", type=int, default=0, choices=[0, 256, 512, 1024, 2048, 4096],
+                    help="pin the tokens of one context handled by one decode-attention workgroup (0: the library's choice)")
     ap.add_argument("--kv-fp8", action="store_true",
                     help="run the 8-bit KV-cache section even in the lean (--no-sweep) mode")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -507,6 +513,8 @@ def main():
     dec_ctx = W.decode_ctx_lens(args.workload, B)
     pre_lens = W.prefill_seq_lens(args.workload, n_prompts)
     st, dec, pre, pre_tables, cu = build_stage(tdp, W, Stage, shape, dec_ctx, pre_lens, i32)
+    if args.decode_span:
+        tdp.tdp_stage_set_decode_span(st.h, args.decode_span)
     stream = torch.cuda.current_stream()
     sargs = (shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ff)
 
@@ -656,9 +664,11 @@ def main():
         emp = empirical_section(tdp, st, shape.n_layers, stream)
         result["empirical_peaks"] = emp
         if roof["bound"] == "hbm":
-            roof["frac_of_measured_scattered_read"] = round(roof["achieved"] / emp["hbm_read_4k_scattered_gbs"], 4)
+            # against the probe that reads the way the kernel does: scattered 4 KiB pieces, non-temporal loads
+            roof["frac_of_measured_scattered_read"] = round(
+                roof["achieved"] / emp["hbm_read_4k_scattered_non_temporal_gbs"], 4)
         # the composite lower bound again, priced at what the probes sustain instead of the published peaks
-        t_min_emp = sum(max(v["alg_bytes_per_launch"] * v["launches_per_step"] / (emp["hbm_read_in_order_gbs"] * 1e9),
+        t_min_emp = sum(max(v["alg_bytes_per_launch"] * v["launches_per_step"] / (emp["hbm_read_in_order_non_temporal_gbs"] * 1e9),
                             v["alg_flops_per_launch"] * v["launches_per_step"] / (emp["mfma_bf16_loop_tflops"] * 1e12))
                         for v in kern.values()) * 1e3
         result["decode"]["composite_t_min_at_measured_ceilings_ms"] = round(t_min_emp, 3)

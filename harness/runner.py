@@ -60,23 +60,30 @@ class Stage:
                                          tdp.BF16 if dtype == torch.bfloat16 else tdp.F32, tdp.DEVICE, rows, cols)
                 del w
 
-    def pools(self, layer):
-        """(K [pages, Hkv, 16, dh], V [pages, Hkv, dh, 16]) zero-copy views: bf16, or the raw codes
-        (uint8) of an 8-bit cache."""
+    def raw_pools(self, layer):
+        """Zero-copy flat views of the layer's K and V pools: bf16, or the raw codes (uint8) of an 8-bit cache."""
         k, v, n = self.tdp.tdp_stage_kv_pool(self.h, layer)
-        sh = self.shape
         view = dev_view_bf16 if self.kv_scales is None else dev_view_u8
-        kt = view(k, n).view(self.num_pages, sh.n_kv_heads, 16, sh.head_dim)
-        vt = view(v, n).view(self.num_pages, sh.n_kv_heads, sh.head_dim, 16)
+        return view(k, n), view(v, n)
+
+    def pools(self, layer):
+        """(K [pages, Hkv, 16, dh], V [pages, Hkv, dh, 16]) in logical coordinates, from the documented
+        layout alone.  V is a zero-copy view.  K is a copy: in memory a key row is cut into 64-byte pieces
+        and piece g of the 16 tokens of a page lies together, [pages, Hkv, row bytes / 64, 16, 64 bytes]."""
+        kf, vf = self.raw_pools(layer)
+        sh = self.shape
+        per_piece = 32 if self.kv_scales is None else 64          # elements in 64 bytes
+        kt = kf.view(self.num_pages, sh.n_kv_heads, sh.head_dim // per_piece, 16, per_piece)
+        kt = kt.permute(0, 1, 3, 2, 4).reshape(self.num_pages, sh.n_kv_heads, 16, sh.head_dim)
+        vt = vf.view(self.num_pages, sh.n_kv_heads, sh.head_dim, 16)
         return kt, vt
 
     POISON_CODE = 0x7F   # the NaN of the 8-bit format
 
     def poison(self):
         for l in range(self.shape.n_layers):
-            k, v = self.pools(l)
-            k.fill_(float("nan") if self.kv_scales is None else self.POISON_CODE)
-            v.fill_(float("nan") if self.kv_scales is None else self.POISON_CODE)
+            for t in self.raw_pools(l):
+                t.fill_(float("nan") if self.kv_scales is None else self.POISON_CODE)
         torch.cuda.synchronize()
 
     def close(self):

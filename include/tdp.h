@@ -133,9 +133,14 @@ TDP_API int tdp_stage_set_weight(tdp_stage* st, int32_t layer, int32_t which, co
 
 /*
  * Raw access to one layer's KV pools, for tests that poison, inject or dump them.
- * Layout:  K pool [num_pages][n_kv_heads][16][head_dim]
- *          V pool [num_pages][n_kv_heads][head_dim][16]   (token slot fastest)
- * of bf16 elements, or of one-byte E4M3 codes when kv_dtype = TDP_KV_FP8_E4M3.
+ * Layout:  K pool [num_pages][n_kv_heads][R / 64][16][64 bytes]   (R = bytes of one key row)
+ *          V pool [num_pages][n_kv_heads][head_dim][16]             (token slot fastest)
+ * of bf16 elements, or of one-byte E4M3 codes when kv_dtype = TDP_KV_FP8_E4M3.  A key row (head_dim
+ * elements, R = 64 ... 256 bytes) is stored in 64-byte pieces, piece g of the page's 16 token slots
+ * together: byte r of the key of (page, head, slot) lies at
+ *   ((page * n_kv_heads + head) * 16 * R) + (r / 64) * 1024 + slot * 64 + r % 64
+ * (what one decode-attention load instruction fetches, 64 bytes of each of 16 tokens, is then four
+ * runs of 256 bytes instead of sixteen half cache lines).
  * Keys are stored after the rotary embedding.  `*bytes` = size of EACH pool.
  */
 TDP_API int tdp_stage_kv_pool(tdp_stage* st, int32_t layer, void** k_dev, void** v_dev, int64_t* bytes);
@@ -270,9 +275,10 @@ TDP_API int tdp_e4m3_to_f32(const uint8_t* codes, float* dst, int64_t n, void* s
  * `stream`, wait for them and return the average milliseconds per launch in *ms_per_launch (host).
  * tdp_probe_hbm_read: reads the first 2^k * 4 KiB of `buf` (dev, 16-byte aligned, at least 512 KiB;
  *   2^k * 4 KiB is the largest such size <= bytes, returned in *bytes_per_launch) exactly once per
- *   launch, 16 bytes per lane per instruction, 16 KiB in flight per wave; scattered = 0 walks the
- *   4 KiB pieces in address order, 1 in a fixed pseudo-random order (how a paged KV cache is read).
- *   Nothing is written to `buf`.
+ *   launch, 16 bytes per lane per instruction, 16 KiB in flight per wave.  pattern bit 0: 0 walks the
+ *   4 KiB pieces in address order, 1 in a fixed pseudo-random order (how a paged KV cache is read);
+ *   bit 1: the loads are marked non-temporal, as the library's own kernels mark data they read once
+ *   (keys and values in decode, weights of a GEMM with a single row of tiles).  Nothing is written to `buf`.
  * tdp_probe_mfma_bf16: `iters` (1..2^22) rounds of sixteen independent 16x16x32 bf16 MFMAs per wave on
  *   register operands, two waves per SIMD on every CU; *flop_per_launch (host) = multiply-adds * 2.
  *   random_operands = 1: operands uniform in (-1, 1), different in every lane and element; 0: the
@@ -280,7 +286,7 @@ TDP_API int tdp_e4m3_to_f32(const uint8_t* codes, float* dst, int64_t n, void* s
  *   power grows with the operand bits that toggle).
  * Errors: TDP_EINVAL (null pointer, size or count out of range), TDP_ENOMEM, TDP_EHIP.
  */
-TDP_API int tdp_probe_hbm_read(const void* buf, int64_t bytes, int32_t scattered, int32_t launches,
+TDP_API int tdp_probe_hbm_read(const void* buf, int64_t bytes, int32_t pattern, int32_t launches,
                                int64_t* bytes_per_launch, float* ms_per_launch, void* stream);
 TDP_API int tdp_probe_mfma_bf16(int32_t iters, int32_t launches, int32_t random_operands, double* flop_per_launch,
                                 float* ms_per_launch, void* stream);

@@ -206,19 +206,22 @@ __global__ __launch_bounds__(256, 3) void attn_decode_kernel(const bf16* __restr
       if constexpr (KV8) {
         // score tile t, row r16 -> token (r16/4)*16 + t*4 + r16%4: page r16/4 of the block, slot t*4 + r16%4
         const int64_t kpage = (r16 >> 2) == 0 ? page[0] : (r16 >> 2) == 1 ? page[1] : (r16 >> 2) == 2 ? page[2] : page[3];
-        const uint8_t* kp = kpool8 + ((kpage * Hkv + kvh) * 16 + (r16 & 3)) * DH + kg * 16;
+        // (K pool: 64-byte pieces of the 16 token rows of a page lie together, piece l at l * 1024)
+        const uint8_t* kp = kpool8 + (kpage * Hkv + kvh) * (16 * DH) + (r16 & 3) * 64 + kg * 16;
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
           for (int l = 0; l < KS / 2; ++l)
-            blk.kf[t >> 1][(t & 1) * (KS / 2) + l] = ld_bf16x8_nt(reinterpret_cast<const bf16*>(kp + (t * 4) * DH + l * 64));
+            blk.kf[t >> 1][(t & 1) * (KS / 2) + l] = ld_bf16x8_nt(reinterpret_cast<const bf16*>(kp + (t * 4) * 64 + l * 1024));
       } else {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
           const int tok = krow0 + t * 4;
-          const bf16* kp = kpool + ((page[tok >> 4 & 1] * Hkv + kvh) * 16 + (tok & 15)) * DH + kg * 8;
+          // (K pool: the 32 channels of k-step kk are one 64-byte piece; piece kk of the page's 16 tokens is
+          // contiguous, so the 16 rows x 64 bytes of one instruction are four runs of 256 bytes)
+          const bf16* kp = kpool + (page[tok >> 4 & 1] * Hkv + kvh) * (16 * DH) + (tok & 15) * 32 + kg * 8;
 #pragma unroll
-          for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8_nt(kp + kk * 32);
+          for (int kk = 0; kk < KS; ++kk) blk.kf[t][kk] = ld_bf16x8_nt(kp + kk * (16 * 32));
         }
       }
     };
@@ -499,6 +502,7 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
   constexpr int CR = DH / 8;     // 16-byte chunks per K row
   constexpr int RWK = DH == 128 ? 1 : 2;  // K rows per 256-byte bank window
   constexpr int NCH = CR / 8;    // chunks of K, and of V^T, per thread per 64-token block
+  constexpr int QP = KV8 ? 8 : 4;  // 8-element chunks per 64-byte piece of a key row in the pool
   __shared__ __attribute__((aligned(16))) bf16 sK[2][2][32 * DH];  // [buffer][32-token half]
   __shared__ __attribute__((aligned(16))) bf16 sV[2][2][DH * 32];
 
@@ -560,11 +564,13 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int ci = tid + 512 * j;
-      const int ksub = ci / (32 * CR), ktok = (ci / CR) % 32, kc = ci % CR;
-      const int64_t kp = ksub ? (ktok < 16 ? page[2] : page[3]) : (ktok < 16 ? page[0] : page[1]);
+      // K: consecutive threads walk the pool in address order - the QP chunks of a 64-byte piece, the 16
+      // tokens of the page, the pieces of the row, the four pages of the block
+      const int kq = ci % QP, kt16 = (ci / QP) % 16, kpiece = (ci / (QP * 16)) % (CR / QP), kpg = ci / (16 * CR);
+      const int64_t kp = page[kpg];
       const int vsub = ci / (DH * 4), vr = (ci >> 2) % DH, vc = ci & 3;
       const int64_t vp = vsub ? (vc < 2 ? page[2] : page[3]) : (vc < 2 ? page[0] : page[1]);
-      const int64_t k_at = ((kp * Hkv + kvh) * 16 + (ktok & 15)) * DH + kc * 8;
+      const int64_t k_at = (kp * Hkv + kvh) * (16 * DH) + (kpiece * 16 + kt16) * (QP * 8) + kq * 8;
       const int64_t v_at = ((vp * Hkv + kvh) * DH + vr) * 16 + (vc & 1) * 8;
       bf16x8 v;
       if constexpr (KV8) {
@@ -596,7 +602,8 @@ __global__ __launch_bounds__(512) void attn_prefill_kernel(const bf16* __restric
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int ci = tid + 512 * j;
-      const int ksub = ci / (32 * CR), ktok = (ci / CR) % 32, kc = ci % CR;
+      const int kq = ci % QP, kt16 = (ci / QP) % 16, kpiece = (ci / (QP * 16)) % (CR / QP), kpg = ci / (16 * CR);
+      const int ksub = kpg >> 1, ktok = (kpg & 1) * 16 + kt16, kc = kpiece * QP + kq;
       st_bf16x8(&sK[buf][ksub][ktok * DH + ((kc ^ ((ktok / RWK) % CR)) << 3)], kreg[j]);
       const int vsub = ci / (DH * 4), vr = (ci >> 2) % DH, vc = ci & 3;
       st_bf16x8(&sV[buf][vsub][vr * 32 + ((vc ^ ((vr >> 2) & 3)) << 3)], vreg[j]);

@@ -4,7 +4,9 @@
 // The KV cache (paper Sec. 2.1: per-token keys and values kept so that a decode step only
 // processes the new token) is paged in fixed-size pages addressed through per-request block
 // tables.  Physical layout per layer:
-//   K pool  [num_pages][n_kv_heads][page_size][head_dim]   (one token's key contiguous)
+//   K pool  [num_pages][n_kv_heads][row bytes / 64][page_size][64 bytes]   (a key row in 64-byte pieces,
+//           piece g of the page's 16 tokens together: what one decode-attention load instruction fetches
+//           is then contiguous, see k_pool_byte)
 //   V pool  [num_pages][n_kv_heads][head_dim][page_size]   (token index fastest)
 // Keys are stored after rotation.  The V layout puts 8 consecutive tokens of one channel in
 // 16 bytes, which is exactly the MFMA operand of the P*V product in both attention kernels.
@@ -276,7 +278,6 @@ __global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv
   const float2* cs = table + (int64_t)pos * half;
   const int per_head = half / 8;  // 16-byte units per half head
   const int rot_heads = n_q_heads + kv.n_kv_heads;
-  bf16* kpool = (bf16*)kv.k_pool;
   bf16* vpool = (bf16*)kv.v_pool;
   for (int w = threadIdx.x; w < rot_heads * per_head; w += THREADS) {
     const int head = w / per_head;
@@ -293,7 +294,10 @@ __global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv
       fra[i] = a[i] * t2.x - b[i] * t2.y;
       frb[i] = a[i] * t2.y + b[i] * t2.x;
     }
-    const int64_t kslot = (((int64_t)page * kv.n_kv_heads + (head - n_q_heads)) * kv.page_size + slot) * dh;
+    // byte offsets of this thread's two 8-channel pieces in the K pool (a piece never straddles a 64-byte cut)
+    const int esz = kv.fp8 ? 1 : 2;
+    const int64_t k_lo = head >= n_q_heads ? k_pool_byte(kv, page, head - n_q_heads, slot, c0 * esz) : 0;
+    const int64_t k_hi = head >= n_q_heads ? k_pool_byte(kv, page, head - n_q_heads, slot, (half + c0) * esz) : 0;
     if (head >= n_q_heads && kv.fp8) {
       // 8-bit cache: the rotated key goes from fp32 straight to its code (one rounding)
       uint2 ca = make_uint2(0u, 0u), cb = make_uint2(0u, 0u);
@@ -304,9 +308,8 @@ __global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv
         cb.x |= f32_to_e4m3(frb[i] / kv.k_scale) << (8 * i);
         cb.y |= f32_to_e4m3(frb[4 + i] / kv.k_scale) << (8 * i);
       }
-      uint8_t* dst = (uint8_t*)kv.k_pool + kslot;
-      *reinterpret_cast<uint2*>(dst + c0) = ca;
-      *reinterpret_cast<uint2*>(dst + half + c0) = cb;
+      *reinterpret_cast<uint2*>((uint8_t*)kv.k_pool + k_lo) = ca;
+      *reinterpret_cast<uint2*>((uint8_t*)kv.k_pool + k_hi) = cb;
       continue;
     }
     bf16x8 ra, rb;
@@ -319,9 +322,8 @@ __global__ __launch_bounds__(THREADS) void rope_kv_kernel(bf16* __restrict__ qkv
       st_bf16x8(hp + c0, ra);
       st_bf16x8(hp + half + c0, rb);
     } else {
-      bf16* dst = kpool + kslot;
-      st_bf16x8(dst + c0, ra);
-      st_bf16x8(dst + half + c0, rb);
+      st_bf16x8(reinterpret_cast<bf16*>((uint8_t*)kv.k_pool + k_lo), ra);
+      st_bf16x8(reinterpret_cast<bf16*>((uint8_t*)kv.k_pool + k_hi), rb);
     }
   }
   const int v_col = (n_q_heads + kv.n_kv_heads) * dh;
@@ -457,7 +459,7 @@ __global__ __launch_bounds__(256) void kv_copy_kernel(int to_pages, bf16* __rest
   bf16* vpool = (bf16*)kv.v_pool;
   for (int w = threadIdx.x; w < kv.n_kv_heads * dh; w += 256) {
     const int kvh = w / dh, c = w % dh;
-    const int64_t ki = (((int64_t)page * kv.n_kv_heads + kvh) * kv.page_size + slot) * dh + c;
+    const int64_t ki = k_pool_byte(kv, page, kvh, slot, c * (kv.fp8 ? 1 : 2)) / (kv.fp8 ? 1 : 2);  // element index
     const int64_t vi = (((int64_t)page * kv.n_kv_heads + kvh) * dh + c) * kv.page_size + slot;
     const int64_t pi = (int64_t)t * kv.n_kv_heads * dh + w;
     if (kv.fp8) {

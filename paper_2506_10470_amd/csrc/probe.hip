@@ -32,6 +32,8 @@ __device__ __forceinline__ uint32_t scatter_index(uint32_t g, int bits) {
 
 // Every piece of the first 2^bits * 4 KiB of buf is read exactly once per launch, 16 bytes per lane
 // per instruction, sixteen instructions in flight per wave.  scattered = 0: pieces in address order.
+// NT: the loads are marked non-temporal (data read once: they need not displace anything in the caches).
+template <bool NT>
 __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint8_t* __restrict__ buf, int bits, int scattered,
                                                              float* __restrict__ sink) {
   const uint32_t wave = (blockIdx.x * 256u + threadIdx.x) >> 6;
@@ -46,7 +48,10 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint8_t* __re
       const uint64_t piece = scattered ? scatter_index(g, bits) : g;
       const uint8_t* p = buf + piece * kPieceBytes + lane * 16;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) r[j * 4 + i] = *reinterpret_cast<const f32x4*>(p + i * 1024);
+      for (int i = 0; i < 4; ++i) {
+        const f32x4* src = reinterpret_cast<const f32x4*>(p + i * 1024);
+        r[j * 4 + i] = NT ? __builtin_nontemporal_load(src) : *src;
+      }
     }
 #pragma unroll
     for (int j = 0; j < kPiecesPerBlock * 4; ++j) acc += r[j];
@@ -123,12 +128,13 @@ int hip_fail(hipError_t e, const char* what) {
 
 extern "C" {
 
-int tdp_probe_hbm_read(const void* buf, int64_t bytes, int32_t scattered, int32_t launches, int64_t* bytes_per_launch,
+int tdp_probe_hbm_read(const void* buf, int64_t bytes, int32_t pattern, int32_t launches, int64_t* bytes_per_launch,
                        float* ms_per_launch, void* stream) {
   if (!buf || !bytes_per_launch || !ms_per_launch) return probe_fail(TDP_EINVAL, "null pointer");
   if (((uintptr_t)buf & 15) != 0) return probe_fail(TDP_EINVAL, "buf must be 16-byte aligned");
   if (launches < 1 || launches > 1000) return probe_fail(TDP_EINVAL, "launches must be in 1..1000");
-  if (scattered != 0 && scattered != 1) return probe_fail(TDP_EINVAL, "scattered must be 0 or 1");
+  if (pattern < 0 || pattern > 3) return probe_fail(TDP_EINVAL, "pattern must be 0..3 (bit 0: scattered, bit 1: non-temporal)");
+  const int scattered = pattern & 1;
   // whole workgroups: 4 waves x 8 blocks x 4 pieces = 128 pieces (512 KiB) each
   constexpr int64_t kMin = 128ll * kPieceBytes;
   if (bytes < kMin) return probe_fail(TDP_EINVAL, "the buffer must hold at least 512 KiB");
@@ -141,8 +147,13 @@ int tdp_probe_hbm_read(const void* buf, int64_t bytes, int32_t scattered, int32_
   hipError_t e = hipMalloc((void**)&sink, sizeof(float));
   if (e != hipSuccess) return hip_fail(e, "hipMalloc");
   e = time_launches(
-      [&] { hbm_read_probe_kernel<<<grid, 256, 0, s>>>((const uint8_t*)buf, bits, scattered, sink); }, launches, s,
-      ms_per_launch);
+      [&] {
+        if (pattern & 2)
+          hbm_read_probe_kernel<true><<<grid, 256, 0, s>>>((const uint8_t*)buf, bits, scattered, sink);
+        else
+          hbm_read_probe_kernel<false><<<grid, 256, 0, s>>>((const uint8_t*)buf, bits, scattered, sink);
+      },
+      launches, s, ms_per_launch);
   (void)hipFree(sink);
   if (e != hipSuccess) return hip_fail(e, "tdp_probe_hbm_read");
   *bytes_per_launch = pieces * kPieceBytes;

@@ -200,11 +200,11 @@ def tdp_e4m3_to_f32(codes, dst, n, stream=None) -> None:
     _check(lib.tdp_e4m3_to_f32(_ptr(codes), _ptr(dst), n, _stream(stream)))
 
 
-def tdp_probe_hbm_read(buf, nbytes: int, scattered: bool, launches: int = 5, stream=None):
+def tdp_probe_hbm_read(buf, nbytes: int, scattered: bool, launches: int = 5, stream=None, non_temporal: bool = False):
     """-> (bytes read per launch, ms per launch)"""
     n, ms = _i64(), C.c_float()
-    _check(lib.tdp_probe_hbm_read(_ptr(buf), nbytes, int(bool(scattered)), launches, C.byref(n), C.byref(ms),
-                                  _stream(stream)))
+    _check(lib.tdp_probe_hbm_read(_ptr(buf), nbytes, int(bool(scattered)) | (2 if non_temporal else 0), launches,
+                                  C.byref(n), C.byref(ms), _stream(stream)))
     return n.value, ms.value
 
 

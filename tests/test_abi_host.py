@@ -127,7 +127,8 @@ def test_probe_entry_points_reject_bad_arguments():
     assert P(4096, 1 << 20, 0, 1, None, C.byref(ms), None) == tdp.EINVAL                # null result
     assert P(4100, 1 << 20, 0, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # misaligned
     assert P(4096, 1 << 18, 0, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # below 512 KiB
-    assert P(4096, 1 << 20, 2, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # pattern
+    assert P(4096, 1 << 20, 4, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # pattern
+    assert P(4096, 1 << 20, -1, 1, C.byref(n), C.byref(ms), None) == tdp.EINVAL
     assert P(4096, 1 << 20, 0, 0, C.byref(n), C.byref(ms), None) == tdp.EINVAL          # launches
     assert P(4096, 1 << 20, 0, 1001, C.byref(n), C.byref(ms), None) == tdp.EINVAL
     M = tdp.lib.tdp_probe_mfma_bf16

@@ -15,10 +15,11 @@ def tdp():
 def test_hbm_read_probe_sizes_and_rates(tdp):
     buf = torch.full(((1 << 30) + 12345,), 7, dtype=torch.uint8, device="cuda")
     for scattered in (False, True):
-        n, ms = tdp.tdp_probe_hbm_read(buf, buf.numel(), scattered, 3)
-        assert n == 1 << 30                     # the largest 2^k * 4 KiB that fits
-        gbs = n / ms / 1e6
-        assert 1000.0 < gbs < 8000.0, (scattered, gbs)
+        for nt in (False, True):
+            n, ms = tdp.tdp_probe_hbm_read(buf, buf.numel(), scattered, 3, non_temporal=nt)
+            assert n == 1 << 30                     # the largest 2^k * 4 KiB that fits
+            gbs = n / ms / 1e6
+            assert 1000.0 < gbs < 8000.0, (scattered, nt, gbs)
     n, ms = tdp.tdp_probe_hbm_read(buf, 3 << 20, True, 2)
     assert n == 2 << 20 and ms > 0
     n, ms = tdp.tdp_probe_hbm_read(buf, 512 << 10, False, 1)       # the smallest size: one workgroup
