@@ -43,8 +43,29 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 MAX_PPS = 4096 // 16 + 1
 
 
+_EMIT = None   # set per test: prints past pytest's capture, so that a long oracle pass is seen to make progress
+
+
 def say(*a):
-    print(*a, file=sys.stderr, flush=True)
+    if _EMIT is not None:
+        _EMIT(" ".join(str(x) for x in a))
+    else:
+        print(*a, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _progress_lines_reach_the_terminal(capsys):
+    """The oracle needs minutes of CPU time per configuration; its per-layer progress lines go to the real
+    stderr (capture suspended for the line), so a runner that watches for output does not take the test
+    for hung."""
+    global _EMIT
+
+    def emit(msg):
+        with capsys.disabled():
+            print(msg, file=sys.stderr, flush=True)
+    _EMIT = emit
+    yield
+    _EMIT = None
 
 
 def to_dev_bf16(a: np.ndarray) -> torch.Tensor:
