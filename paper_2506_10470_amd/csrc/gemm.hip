@@ -193,7 +193,10 @@ __device__ __forceinline__ bool gemm_tile_of_block(const GemmParams& p, int& til
 // rows: the decode sizes) every weight byte is read by exactly one workgroup, so keeping it in L2
 // only evicts what is shared - the activation panel, the split-K partials.  Measured at M = 32 ... 256
 // on the 70B shapes: +6 to +12 % on the down projection, +2 to +8 % on gate/up, +1 to +4 % on QKV and
-// O; with two or more tile rows the weights are shared through L2 and the hint costs 5-10 %.
+// O.  With more tile rows the weights are shared through L2 and the hint costs 5-10 % on the large
+// shapes; the one exception that pays is two tile rows on a wide projection without split-K (gate/up at
+// M = 512: the two readers of a weight tile are neighbours in one super-block and run at the same time,
+// so the second read still finds the line): -1.8 %.
 template <int BM, int NS, int TM, int TN, int BN = 256, bool WNT = false>
 __global__ __launch_bounds__((BM / (TM * 32)) * (BN / 32 / TN) * 64) void gemm_mi16_kernel(const GemmParams p) {
   constexpr int BK = 32;
@@ -611,8 +614,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
             a.M, (long long)a.Npad, (long long)a.Kpad, t, p.tiles_m, p.tiles_n, splits, p.k_tiles_per_split, p.sb_m,
             p.sb_n);
   dim3 grid(((p.n_sb * splits + 7) / 8) * 8 * p.sb_m * p.sb_n);
-  // a single row of tiles reads every weight byte once: request them as non-temporal
-  const bool wnt = p.tiles_m == 1;
+  // a single row of tiles reads every weight byte once: request them as non-temporal (also two rows of a
+  // wide projection, see the kernel's comment)
+  const bool wnt = p.tiles_m == 1 || (p.tiles_m == 2 && a.Npad >= 32768 && splits == 1);
   switch (t * 2 + (wnt ? 1 : 0)) {
     case 2: gemm_mi16_kernel<256, 4, 4, 4, 256, false><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
     case 3: gemm_mi16_kernel<256, 4, 4, 4, 256, true><<<grid, dim3(256), ti.lds_bytes, s>>>(p); break;
