@@ -524,6 +524,34 @@ def test_decode_every_span_length(tdp, span):
             tdp.tdp_stage_set_decode_span(st.h, 300)
 
 
+@pytest.mark.parametrize("shape", ["tiny", "tiny_h128", "tiny_gqa"])
+def test_import_puts_every_element_where_the_documented_layout_says(tdp, shape):
+    """The pools' layout is part of the ABI (tdp_stage_kv_pool): keys in 64-byte pieces, piece g of a page's
+    16 tokens together; values with the token slot fastest.  Imported keys and values are found, bit
+    for bit, at the addresses the header's formula gives (Stage.pools undoes the piece order by that
+    formula), nothing else is touched, and export returns them."""
+    sh = W.SHAPES[shape]
+    lens = np.array([1, 16, 37, 5, 64], dtype=np.int64)
+    batch = W.make_decode_batch(lens)
+    with Stage(tdp, sh, batch.num_pages, len(lens), 0, 0, batch.tables.shape[1], load_weights=False) as st:
+        st.poison()
+        caches = import_kv(tdp, st, lens, batch.tables, 5)
+        mk, mv = written_slot_mask(st, batch.tables, np.zeros(len(lens), dtype=np.int64), lens)
+        for l in range(sh.n_layers):
+            k_pool, v_pool = (t.float().cpu() for t in st.pools(l))
+            assert bool(torch.isnan(k_pool[~mk]).all()) and bool(torch.isnan(v_pool[~mv]).all())
+            for b in range(len(lens)):
+                k_ref, v_ref = caches[b][l]
+                for p in range(int(lens[b])):
+                    page, slot = int(batch.tables[b, p // 16]), p % 16
+                    assert np.array_equal(k_pool[page, :, slot, :].numpy().astype(np.float64), k_ref[p])
+                    assert np.array_equal(v_pool[page, :, :, slot].numpy().astype(np.float64), v_ref[p])
+            kx, vx, cu = export_kv(tdp, st, lens, batch.tables, l)
+            for b in range(len(lens)):
+                assert np.array_equal(kx[cu[b]:cu[b + 1]], caches[b][l][0])
+                assert np.array_equal(vx[cu[b]:cu[b + 1]], caches[b][l][1])
+
+
 @pytest.mark.parametrize("span", [0, 256, 4096])
 def test_decode_contexts_far_beyond_the_benchmark(tdp, span):
     """Contexts of up to 20,000 tokens (the benchmark stops at 4096): dozens of spans per request
